@@ -1,0 +1,166 @@
+/* mmsp.h -- C ABI of the MI355X (gfx950) attention library for one rank of Multi-Modal
+ * Sequence Parallelism (MM-SP; paper Sec. 4.2 "Multi-Modal Sequence Parallelism Training
+ * Mode" and the figure comparing RingAttention, ZigZag-RingAttn and 2D-Attention).
+ *
+ * One rank of a zigzag ring holds query chunks r and 2N-1-r of a packed sequence and,
+ * over N ring steps, attends them against the K/V block of every rank.  Each step is a
+ * flash-style partial attention that yields (O_part, LSE_part); partials are combined by a
+ * log-sum-exp merge; the backward of each step yields dQ (accumulated over steps) and the
+ * step's dK/dV.  The Ulysses (head-sharded) mode is the same calls on the whole packed
+ * sequence for a subset of heads, with a document-causal mask given by cu_seqlens.
+ *
+ * General rules
+ *   - C99 types only.  Pointers are DEVICE pointers unless marked "host".
+ *   - The caller owns every buffer and the HIP stream.  The library allocates, frees and
+ *     retains nothing.  Work is enqueued on `hip_stream` (a hipStream_t; NULL = the null
+ *     stream) and the call returns without synchronising.  Calls on one stream run in order.
+ *   - Every call returns an mmsp_status.  On any status other than MMSP_OK nothing has been
+ *     enqueued.  The library never aborts and never throws.  mmsp_last_error() returns a
+ *     thread-local, statically stored message for the last failing call on this thread.
+ *   - Tensor layouts (d = head_dim, contiguous, always the fastest axis):
+ *       Q                       [rows, n_q_heads, d], element strides q_tok_stride / q_head_stride
+ *       K, V                    [rows, n_kv_heads, d], element strides kv_tok_stride / kv_head_stride
+ *       O (partial, running, final), dO, dQ   dense [rows, n_q_heads, d]
+ *       dK, dV                  dense [rows, n_kv_heads, d]
+ *       LSE, delta              [n_q_heads, rows], head stride lse_head_stride (elements)
+ *     Q, K, V, dO and the final O are in io_dtype (bf16 or f32).  Partial / running O,
+ *     LSE, delta, dQ, dK and dV are always f32.
+ *   - Row indices in mmsp_block are relative to the base pointers: query-side buffers
+ *     (Q, O, dO, dQ, LSE, delta) are indexed by the rank-local row, key-side buffers
+ *     (K, V, dK, dV) by the row inside the visiting K/V block.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - Supported: head_dim 64 or 128; bf16 needs head_dim 128 for the matrix-core path.
+ */
+#ifndef MMSP_H
+#define MMSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MMSP_OK = 0,
+  MMSP_ERR_INVALID_ARG = 1,        /* null pointer, bad range, bad divisibility            */
+  MMSP_ERR_UNSUPPORTED = 2,        /* head_dim / dtype combination with no kernel          */
+  MMSP_ERR_WORKSPACE_TOO_SMALL = 3,
+  MMSP_ERR_DEVICE = 4              /* launch failed; text in mmsp_last_error()             */
+} mmsp_status;
+
+/* Which (query row, key row) pairs of a block are visible.  "Position" is the index of a
+ * row in the coordinate system named by q_pos0 / k_pos0 (see mmsp_block). */
+typedef enum {
+  MMSP_MASK_FULL = 0,        /* every query row sees every key row of the block           */
+  MMSP_MASK_CAUSAL_DIAG = 1, /* query at position p sees keys at positions <= p           */
+  MMSP_MASK_NONE = 2         /* nothing is visible: O_part = 0, LSE_part = -inf, grads 0  */
+} mmsp_mask;
+
+typedef enum { MMSP_BF16 = 0, MMSP_F32 = 1 } mmsp_dtype;
+
+/* Problem shape.  Plain data, read during the call only. */
+typedef struct {
+  int32_t n_q_heads;
+  int32_t n_kv_heads;        /* must divide n_q_heads                                     */
+  int32_t head_dim;          /* 64 or 128                                                 */
+  int32_t io_dtype;          /* mmsp_dtype of Q, K, V, dO and the final O                 */
+  float   softmax_scale;     /* multiplies Q.K before the softmax; callers pass 1/sqrt(d) */
+  int64_t q_tok_stride, q_head_stride;     /* element strides of Q                        */
+  int64_t kv_tok_stride, kv_head_stride;   /* element strides of K and of V               */
+  int64_t lse_head_stride;   /* elements between consecutive heads of LSE / delta arrays  */
+} mmsp_shape;
+
+/* The sub-block of (local queries) x (visiting keys) that one call works on. */
+typedef struct {
+  int64_t q_row0, n_q;       /* query rows [q_row0, q_row0 + n_q)                          */
+  int64_t k_row0, n_k;       /* key rows   [k_row0, k_row0 + n_k) of the visiting block    */
+  int64_t q_pos0, k_pos0;    /* position of row q_row0 / k_row0; consecutive rows have
+                                consecutive positions.  Used by CAUSAL_DIAG and cu_seqlens */
+  int32_t mask;              /* mmsp_mask                                                  */
+  int32_t n_docs;            /* number of documents in cu_seqlens (0 when it is NULL)      */
+  const int32_t* cu_seqlens; /* device, [n_docs + 1], ascending, [0] = 0; NULL = one
+                                document.  A pair is visible only if both positions fall
+                                in the same document (packed variable-length inputs).     */
+} mmsp_block;
+
+/* Zigzag ("both ends") sharding -- Sec. 4.2 "MM-SP workflow": the sequence is cut into 2N
+ * equal chunks and rank r takes chunk r and chunk 2N-1-r, so every rank owns the same
+ * number of causal pairs.  chunk_ids (host, 2 ints) receives {r, 2N-1-r}.
+ * local_to_global (host, T/N int64, may be NULL) receives the global token index of each
+ * local row (ascending).  INVALID_ARG if T <= 0, N <= 0, T % (2N) != 0 or rank not in [0,N). */
+mmsp_status mmsp_zigzag_layout(int64_t T, int32_t N, int32_t rank,
+                               int32_t chunk_ids[2], int64_t* local_to_global);
+
+/* Ring plan for the same sharding (the per-round schedule drawn in the ZigZag row of the
+ * comparison figure).  At step s rank r is visited by the K/V block of rank
+ * src = (r - s) mod N.  *blk (host) receives the only sub-block with visible pairs:
+ *   src == r: all 2C rows x all 2C keys, CAUSAL_DIAG on local positions;
+ *   src <  r: all 2C rows x the first C keys, FULL;
+ *   src >  r: the last C rows x all 2C keys, FULL.
+ * cu_seqlens is left NULL.  INVALID_ARG as above or if step not in [0,N). */
+mmsp_status mmsp_zigzag_plan(int64_t T, int32_t N, int32_t rank, int32_t step,
+                             int32_t* src_rank, mmsp_block* blk);
+
+/* Bytes of device workspace the step calls need for these extents (currently 0: the
+ * kernels keep all intermediate state in registers and LDS).  `backward` != 0 asks for
+ * mmsp_attn_step_bwd. */
+size_t mmsp_workspace_bytes(const mmsp_shape* shape, int64_t n_q_max, int64_t n_k_max, int backward);
+
+/* One ring step, forward (the "local attention computation within each SP group rank" of
+ * the comparison figure):  for each query head h and query row i of the block,
+ *   S_j = softmax_scale * Q[i,h,:] . K[j,kv(h),:]  over the visible keys j of the block,
+ *   LSE_part = ln sum_j exp(S_j),  O_part = sum_j exp(S_j - LSE_part) V[j,kv(h),:].
+ * accumulate == 0: o and lse are overwritten with (O_part, LSE_part) for rows of the block.
+ * accumulate != 0: o and lse hold the running result and the log-sum-exp merge with the
+ *   partial is applied in the kernel's epilogue (same arithmetic as mmsp_attn_merge).
+ * Rows outside [q_row0, q_row0+n_q) are not touched.  A row that sees nothing gets
+ * O_part = 0, LSE_part = -inf (and leaves a running result unchanged).
+ * workspace may be NULL when mmsp_workspace_bytes() is 0. */
+mmsp_status mmsp_attn_step_fwd(const mmsp_shape* shape, const mmsp_block* blk,
+                               const void* q, const void* k, const void* v,
+                               float* o, float* lse, int accumulate,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Log-sum-exp merge of a partial into the running result on rows [row0, row0+n_rows)
+ * (how the per-round results of ring attention are combined; the paper leaves the formula
+ * implicit):  L' = ln(e^L + e^Lp),  O' = e^(L-L') O + e^(Lp-L') Op,  with a side whose LSE
+ * is -inf contributing nothing.  o_acc / lse_acc are updated in place.
+ * If o_final != NULL it also receives O' cast to io_dtype (dense [rows, n_q_heads, d]).
+ * With o_part == NULL and lse_part == NULL nothing is merged and only the cast is done
+ * (o_final must then be non-NULL). */
+mmsp_status mmsp_attn_merge(const mmsp_shape* shape, int64_t row0, int64_t n_rows,
+                            float* o_acc, float* lse_acc,
+                            const float* o_part, const float* lse_part,
+                            void* o_final, void* hip_stream);
+
+/* delta[h,i] = sum_c dO[i,h,c] * O_final[i,h,c] on rows [row0, row0+n_rows): the
+ * softmax-backward row term, computed once per rank from the final merged O. */
+mmsp_status mmsp_attn_delta(const mmsp_shape* shape, int64_t row0, int64_t n_rows,
+                            const void* o_final, const void* d_o, float* delta, void* hip_stream);
+
+/* One ring step, backward.  With P = exp(S - lse_final) on visible pairs (0 elsewhere):
+ *   dV[j,kv] (+)= sum_{h in group} sum_i P dO[i,h,:]
+ *   dS = P * (dO[i,h,:] . V[j,kv,:] - delta[h,i])
+ *   dK[j,kv] (+)= softmax_scale * sum_{h in group} sum_i dS Q[i,h,:]
+ *   dQ[i,h]   += softmax_scale * sum_j dS K[j,kv,:]
+ * lse_final / delta are those of the completed forward (all steps merged).
+ * compute_delta != 0: delta for the block's query rows is first computed from o_final and
+ *   d_o (as mmsp_attn_delta) and stored in `delta`; otherwise o_final may be NULL.
+ * dq_acc is always accumulated into (the caller zeroes it before the first step).
+ * accumulate_dkdv == 0 overwrites dk/dv rows [k_row0, k_row0+n_k); != 0 adds to them.
+ * Results are bit-identical from run to run (no floating-point atomics). */
+mmsp_status mmsp_attn_step_bwd(const mmsp_shape* shape, const mmsp_block* blk,
+                               const void* q, const void* k, const void* v,
+                               const void* o_final, const void* d_o,
+                               const float* lse_final, float* delta, int compute_delta,
+                               float* dq_acc, float* dk, float* dv, int accumulate_dkdv,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Message for the last non-OK status returned on the calling thread ("" if none). */
+const char* mmsp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMSP_H */

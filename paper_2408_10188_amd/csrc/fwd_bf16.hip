@@ -1,0 +1,213 @@
+// Forward ring step on bf16 matrix cores, head_dim 128.
+//
+// Workgroup = 4 wavefronts = 128 query rows of one head; wavefront w owns 32 rows and keeps
+// their Q (as MFMA B operands, 32 VGPRs), O^T accumulator (128 d x 32 queries, 64 VGPRs) and
+// softmax statistics in registers for the whole call.  K/V stream through LDS in 64-key
+// tiles, double buffered, fetched from HBM/L2 into registers one tile ahead.
+//   S^T[key][query] = K . Q^T            (A = K tile from LDS, B = Q registers)
+//   online softmax down the key axis, which is in-lane in S^T's register layout
+//   O^T[d][query]  += V^T . P^T          (A = V^T tile from LDS, B = P^T straight from registers)
+// Tiles wholly outside every row's visible key interval are skipped; only tiles that cut an
+// interval boundary (the causal diagonal, a document start) pay for masking.
+#include "mfma_tiles.h"
+
+namespace mmsp {
+namespace {
+
+constexpr int kBM = 128;   // query rows per workgroup
+constexpr int kBN = 64;    // keys per tile
+
+template <bool kAccum>
+__global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(StepArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // [2][K TileN | V TileT]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  // heaviest (latest) query tiles first: under the causal mask they have the most keys
+  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;
+  const int h = blockIdx.y, kvh = h / a.group;
+  const int tile_row0 = qt * kBM;
+  const int row = tile_row0 + wave * 32 + col;          // block-relative query row of this lane
+  const bool live = row < a.n_q;
+  const int rowc = min(row, a.n_q - 1);
+
+  // visible key interval of this lane's row, and of the workgroup / wavefront extremes
+  int lo, hi;
+  key_interval_of_row(a, rowc, lo, hi);
+  int t_lo, t_hi, dummy;
+  key_interval_of_row(a, tile_row0, t_lo, dummy);
+  key_interval_of_row(a, min(tile_row0 + kBM, a.n_q) - 1, dummy, t_hi);
+  int w_lo_max, w_hi_min;                               // wavefront: largest lo, smallest hi
+  {
+    const int wr0 = min(tile_row0 + wave * 32, a.n_q - 1), wr1 = min(tile_row0 + wave * 32 + 31, a.n_q - 1);
+    key_interval_of_row(a, wr0, dummy, w_hi_min);
+    key_interval_of_row(a, wr1, w_lo_max, dummy);
+  }
+  const int kt0 = t_lo / kBN, kt1 = t_hi >= t_lo ? t_hi / kBN : kt0 - 1;   // inclusive tile range
+
+  // Q as B operands: k-step ks covers d = ks*16 .. +16, this lane holds 8 of them
+  u32x4 qreg[8];
+  {
+    const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q) + (int64_t)(a.q_row0 + rowc) * a.q_ts +
+                         (int64_t)h * a.q_hs + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const u32x4*>(qp + ks * 16);
+  }
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+  float m = -INFINITY;       // running max of the raw (unscaled) scores of this query
+  float l = 0.f;             // this lane's share of the running sum (its 32 of every 64 keys)
+  const float c = a.scale * kLog2e;
+
+  const uint16_t* kbase = reinterpret_cast<const uint16_t*>(a.k) + (int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs;
+  const uint16_t* vbase = reinterpret_cast<const uint16_t*>(a.v) + (int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs;
+
+  TileRegs kr, vr;
+  if (kt0 <= kt1) {
+    tile_load(kr, kbase, a.kv_ts, kt0 * kBN, a.n_k, tid);
+    tile_load(vr, vbase, a.kv_ts, kt0 * kBN, a.n_k, tid);
+    tile_store_n(kr, smem, tid);
+    tile_store_t(vr, smem + kTileBytes, tid);
+  }
+  __syncthreads();
+
+  int buf = 0;
+  for (int kt = kt0; kt <= kt1; ++kt) {
+    const char* ktile = smem + buf * 2 * kTileBytes;
+    const char* vtile = ktile + kTileBytes;
+    const bool more = kt < kt1;
+    if (more) {
+      tile_load(kr, kbase, a.kv_ts, (kt + 1) * kBN, a.n_k, tid);
+      tile_load(vr, vbase, a.kv_ts, (kt + 1) * kBN, a.n_k, tid);
+    }
+    const int k0 = kt * kBN;
+
+    // ---- S^T = K Q^T : two 32-key blocks ----
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) s[kb] = mfma32(tile_n_read(ktile, kb, ks, lane), qreg[ks], s[kb]);
+    }
+
+    // ---- mask (only tiles that cut an interval boundary) ----
+    if (k0 < w_lo_max || k0 + kBN - 1 > w_hi_min) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = k0 + kb * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
+          if (key < lo || key > hi) s[kb][i] = -INFINITY;
+        }
+    }
+
+    // ---- online softmax along keys ----
+    float mx = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m, mx);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f((m - m_use) * c);    // m = -inf -> 0
+    const float neg_mc = -m_use * c;
+    m = m_new;
+    float psum = 0.f;
+    u32x4 pb[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      float p[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        p[i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], c, neg_mc));
+        psum += p[i];
+      }
+      pb[kb * 2 + 0] = mk4(pack2(p[0], p[1]), pack2(p[2], p[3]), pack2(p[4], p[5]), pack2(p[6], p[7]));
+      pb[kb * 2 + 1] = mk4(pack2(p[8], p[9]), pack2(p[10], p[11]), pack2(p[12], p[13]), pack2(p[14], p[15]));
+    }
+    l = l * alpha + psum;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+    }
+
+    // ---- O^T += V^T P^T ----
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int db = 0; db < 4; ++db) oacc[db] = mfma32(tile_t_read(vtile, db, g, lane), pb[g], oacc[db]);
+
+    if (more) {
+      char* nk = smem + (buf ^ 1) * 2 * kTileBytes;
+      tile_store_n(kr, nk, tid);
+      tile_store_t(vr, nk + kTileBytes, tid);
+    }
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // ---- epilogue ----
+  l += __shfl_xor(l, 32);
+  const bool empty = !(l > 0.f);
+  const float inv = empty ? 0.f : 1.f / l;
+  const float lse_part = empty ? -INFINITY : (m * c + __builtin_amdgcn_logf(l)) * kLn2;   // v_log_f32 is log2
+  if (!live) return;
+  const int64_t r = a.q_row0 + row;
+  float* op = a.o + (r * a.Hq + h) * 128 + half * 4;
+  float* lp = a.lse + (int64_t)h * a.lse_hs + r;
+  float wa = 0.f, wb = inv;
+  if (kAccum) {
+    const float la = *lp;
+    const float mm = fmaxf(la, lse_part);
+    if (mm == -INFINITY) return;                        // both sides empty
+    const float ea = __expf(la - mm), eb = __expf(lse_part - mm);
+    const float tot = ea + eb;
+    wa = ea / tot;
+    wb = eb / tot * inv;
+    if (half == 0) *lp = mm + __logf(tot);
+  } else {
+    if (half == 0) *lp = lse_part;
+  }
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      float4* dst = reinterpret_cast<float4*>(op + db * 32 + g4 * 8);
+      float4 o = make_float4(oacc[db][g4 * 4 + 0] * wb, oacc[db][g4 * 4 + 1] * wb, oacc[db][g4 * 4 + 2] * wb,
+                             oacc[db][g4 * 4 + 3] * wb);
+      if (kAccum) {
+        const float4 old = *dst;
+        o.x += wa * old.x; o.y += wa * old.y; o.z += wa * old.z; o.w += wa * old.w;
+      }
+      *dst = o;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_fwd_bf16(const StepArgs& a, hipStream_t stream) {
+  const dim3 g((a.n_q + kBM - 1) / kBM, a.Hq), b(256);
+  const size_t smem = 4 * kTileBytes;   // two buffers of (K, V^T)
+  if (a.accumulate) {
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_bf16_kernel<true>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (attr != hipSuccess) return attr;
+    fwd_bf16_kernel<true><<<g, b, smem, stream>>>(a);
+  } else {
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_bf16_kernel<false>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (attr != hipSuccess) return attr;
+    fwd_bf16_kernel<false><<<g, b, smem, stream>>>(a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace mmsp

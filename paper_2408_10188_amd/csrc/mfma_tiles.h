@@ -1,0 +1,119 @@
+// Building blocks shared by the bf16 matrix-core kernels: vector types, the 32x32x16 MFMA
+// wrapper, and the two LDS tile layouts with their global->LDS staging.
+//
+// MFMA v_mfma_f32_32x32x16_bf16 (one wavefront, C[32x32] += A[32x16] * B[16x32]):
+//   A operand: lane L holds row (L % 32), k = (L / 32) * 8 .. +8      (8 consecutive k)
+//   B operand: lane L holds col (L % 32), k = (L / 32) * 8 .. +8
+//   C/D:       lane L holds col (L % 32), rows (i / 4) * 8 + (L / 32) * 4 + (i % 4), i = 0..15
+// All kernels compute "transposed" products so that the index a softmax reduces over (keys
+// in the forward and dQ kernels, queries in the dK/dV kernel) lies along C's rows, i.e. inside
+// a lane, and so that C's register layout can be fed back as a B operand: for MFMA k-slot
+// (half = L / 32, j = 0..7) of the k-step that consumes C registers 8t..8t+7, the row index is
+//   16 t + (j / 4) * 8 + half * 4 + (j % 4).
+// The other operand of that second product (V^T, K^T, Q^T, dO^T) is staged in LDS in exactly
+// this permuted order ("TileT"), so the sum over k pairs matching rows.
+#pragma once
+#include "common.h"
+
+namespace mmsp {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+
+__device__ __forceinline__ f32x16 mfma32(const u32x4& a, const u32x4& b, const f32x16& c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ u32x4 mk4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  u32x4 r = {a, b, c, d};
+  return r;
+}
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  f32x2 x = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+}
+
+// ---------------------------------------------------------------------------------------
+// TileN: a [64 rows][128 cols] bf16 tile in its natural orientation (row = token, col = d),
+// 256 bytes per row, 16-byte chunks XOR-swizzled by (row & 15) so that the 16 lanes of a
+// ds_read_b128 phase, which read the same chunk of 16 consecutive rows, hit distinct banks.
+// Used as an MFMA A operand whose k index runs along d.
+// ---------------------------------------------------------------------------------------
+constexpr int kTileBytes = 64 * 128 * 2;     // 16 KiB, both layouts
+
+__device__ __forceinline__ int tile_n_offset(int row, int chunk /*0..15*/) {
+  return row * 256 + ((chunk ^ (row & 15)) << 4);
+}
+// A operand for rows [rb*32, rb*32+32), k-step ks (d = ks*16 .. +16)
+__device__ __forceinline__ u32x4 tile_n_read(const char* tile, int rb, int ks, int lane) {
+  const int row = rb * 32 + (lane & 31);
+  return *reinterpret_cast<const u32x4*>(tile + tile_n_offset(row, ks * 2 + (lane >> 5)));
+}
+
+// ---------------------------------------------------------------------------------------
+// TileT: the same 64x128 tile transposed, [128 d][64 token slots], 128 bytes per row.  Token
+// t of the tile sits in slot (t & ~15) | swap_bits_2_3(t & 15), which is the k-slot order
+// described above; 16-byte chunks are XOR-swizzled by (d >> 1) & 7.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int tile_t_offset(int d, int chunk /*0..7*/) {
+  return d * 128 + ((chunk ^ ((d >> 1) & 7)) << 4);
+}
+// A operand for d rows [db*32, db*32+32), k-step g (tokens 16g .. 16g+16 in permuted order)
+__device__ __forceinline__ u32x4 tile_t_read(const char* tile, int db, int g, int lane) {
+  const int d = db * 32 + (lane & 31);
+  return *reinterpret_cast<const u32x4*>(tile + tile_t_offset(d, g * 2 + (lane >> 5)));
+}
+
+// Staging registers for one 64x128 tile and 256 threads: thread t owns tokens
+// 4*(t/16) .. +4 and d-chunk (t%16)*8 .. +8  ->  four 16-byte global loads, each row of the
+// tile being read by 16 consecutive lanes (256 contiguous bytes).
+struct TileRegs { u32x4 r[4]; };
+
+// rows are clamped to [0, n_rows-1] so that every load is in bounds; clamped duplicates are
+// masked (or never stored) by the caller.
+__device__ __forceinline__ void tile_load(TileRegs& t, const uint16_t* base, int64_t row_stride, int row0, int n_rows,
+                                          int tid) {
+  const int tok = (tid >> 4) * 4, dc = tid & 15;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = min(row0 + tok + r, n_rows - 1);
+    t.r[r] = *reinterpret_cast<const u32x4*>(base + (int64_t)row * row_stride + dc * 8);
+  }
+}
+
+__device__ __forceinline__ void tile_store_n(const TileRegs& t, char* tile, int tid) {
+  const int tok = (tid >> 4) * 4, dc = tid & 15;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) *reinterpret_cast<u32x4*>(tile + tile_n_offset(tok + r, dc)) = t.r[r];
+}
+
+__device__ __forceinline__ uint32_t comp(const u32x4& v, int i) { return v[i]; }   // i constant after unrolling
+
+__device__ __forceinline__ void tile_store_t(const TileRegs& t, char* tile, int tid) {
+  const int kg = tid >> 4, dc = tid & 15;
+  // tokens 4kg..4kg+3: 16-group g16 = kg/4, offset bits (b3,b2) = ((kg%4)>>1, (kg%4)&1);
+  // slot = b2*8 + b3*4 + (0..3)  ->  chunk = g16*2 + b2, byte offset inside the chunk = b3*8
+  const int chunk = (kg >> 2) * 2 + (kg & 1);
+  const int sub = ((kg >> 1) & 1) * 8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int d = dc * 8 + e;
+    const int wi = e >> 1;
+    u32x2 out;
+    if (e & 1) {   // high halves
+      out.x = __builtin_amdgcn_perm(comp(t.r[1], wi), comp(t.r[0], wi), 0x07060302u);
+      out.y = __builtin_amdgcn_perm(comp(t.r[3], wi), comp(t.r[2], wi), 0x07060302u);
+    } else {       // low halves
+      out.x = __builtin_amdgcn_perm(comp(t.r[1], wi), comp(t.r[0], wi), 0x05040100u);
+      out.y = __builtin_amdgcn_perm(comp(t.r[3], wi), comp(t.r[2], wi), 0x05040100u);
+    }
+    *reinterpret_cast<u32x2*>(tile + tile_t_offset(d, chunk) + sub) = out;
+  }
+}
+
+}  // namespace mmsp

@@ -1,0 +1,107 @@
+"""Shared plumbing of the GPU parity tests: seeded inputs -> device tensors, one virtual rank
+through the C-ABI, and the matching fp64 oracle calls.  No arithmetic of the method lives here."""
+import math
+
+import numpy as np
+import torch
+
+from oracle import mmsp_oracle as orc
+from paper_2408_10188_amd import binding as B
+from paper_2408_10188_amd import ring, synth
+
+DEV = "cuda:0"
+
+
+def to_dev(x, bf16):
+    """float32 numpy (bf16-representable when bf16=True) -> device tensor in the io dtype."""
+    if bf16:
+        bits = synth.bf16_bits(x)
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(DEV)
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(DEV)
+
+
+def to_host64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+class RankProblem:
+    """Inputs of one zigzag configuration, generated per chunk; holds host fp32 copies (exactly
+    the bits the device sees) and device tensors for one rank."""
+
+    def __init__(self, cfg, heads_kv=None):
+        self.cfg = cfg
+        self.bf16 = cfg["dtype"] == "bf16"
+        self.N, self.C = cfg["N"], cfg["C"]
+        self.T = 2 * self.N * self.C
+        self.Hq, self.Hkv, self.d = cfg["Hq"], cfg["Hkv"], cfg["d"]
+        self.scale = 1.0 / math.sqrt(self.d)
+        g = lambda name, c, H, sig: synth.chunk(name, c, self.C, H, self.d, sig, cfg["seed"], self.bf16)
+        n_chunks = 2 * self.N
+        self.K = np.stack([g("k", c, self.Hkv, cfg["sigma"]) for c in range(n_chunks)])   # [2N, C, Hkv, d]
+        self.V = np.stack([g("v", c, self.Hkv, cfg["sigma"]) for c in range(n_chunks)])
+        self._g = g
+        zz = np.array([[r, 2 * self.N - 1 - r] for r in range(self.N)])
+        self.k_zz = to_dev(self.K[zz].reshape(self.N, 2 * self.C, self.Hkv, self.d), self.bf16)
+        self.v_zz = to_dev(self.V[zz].reshape(self.N, 2 * self.C, self.Hkv, self.d), self.bf16)
+
+    def K_full(self):
+        return self.K.reshape(self.T, self.Hkv, self.d)
+
+    def V_full(self):
+        return self.V.reshape(self.T, self.Hkv, self.d)
+
+    def rank_inputs(self, rank):
+        c0, c1 = rank, 2 * self.N - 1 - rank
+        q = np.concatenate([self._g("q", c0, self.Hq, self.cfg["sigma"]), self._g("q", c1, self.Hq, self.cfg["sigma"])])
+        do = np.concatenate([self._g("do", c0, self.Hq, 1.0), self._g("do", c1, self.Hq, 1.0)])
+        return q, do
+
+    def run_gpu(self, rank, q, do=None, fused_merge=True):
+        """Forward (and backward when do is given) of one rank through the C-ABI."""
+        n = 2 * self.C
+        qd = to_dev(q, self.bf16)
+        io = B.MMSP_BF16 if self.bf16 else B.MMSP_F32
+        shape = ring.shape_for(qd, self.k_zz, io, n, self.scale)
+        o_acc = torch.empty(n, self.Hq, self.d, dtype=torch.float32, device=DEV)
+        lse = torch.empty(self.Hq, n, dtype=torch.float32, device=DEV)
+        o_final = torch.empty_like(qd)
+        o_part = lse_part = None
+        if not fused_merge:
+            o_part, lse_part = torch.empty_like(o_acc), torch.empty_like(lse)
+        ring.rank_forward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, o_acc, lse, o_final,
+                          fused_merge=fused_merge, o_part=o_part, lse_part=lse_part)
+        out = dict(o_acc=o_acc, lse=lse, o_final=o_final)
+        if do is not None:
+            dod = to_dev(do, self.bf16)
+            delta = torch.empty_like(lse)
+            dq = torch.zeros_like(o_acc)
+            dk = torch.zeros(self.N, n, self.Hkv, self.d, dtype=torch.float32, device=DEV)
+            dv = torch.zeros_like(dk)
+            ring.rank_backward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, o_final, dod, lse, delta, dq, dk, dv)
+            out.update(delta=delta, dq=dq, dk_zz=dk, dv_zz=dv)
+        torch.cuda.synchronize()
+        return out
+
+    def unzigzag(self, x_zz):
+        """[N, 2C, ...] in zigzag order -> [T, ...] in sequence order (host numpy)."""
+        x = x_zz.reshape(self.N, 2, self.C, *x_zz.shape[2:])
+        out = np.empty((2 * self.N, self.C, *x_zz.shape[2:]), dtype=x_zz.dtype)
+        for r in range(self.N):
+            out[r] = x[r, 0]
+            out[2 * self.N - 1 - r] = x[r, 1]
+        return out.reshape(self.T, *x_zz.shape[2:])
+
+
+def max_abs(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    both_inf = np.isinf(a) & np.isinf(b) & (np.sign(a) == np.sign(b))
+    diff = np.where(both_inf, 0.0, np.abs(a - b))
+    return float(np.nanmax(diff)) if diff.size else 0.0
+
+
+def oracle_rows(prob, q_rows, q_pos, do_rows=None, heads=None, cu=None):
+    """Path A of the oracle for the given query rows (positions q_pos in the full sequence)."""
+    K, V = prob.K_full().astype(np.float64), prob.V_full().astype(np.float64)
+    return orc.causal_attention(q_rows.astype(np.float64), K, V, prob.scale, cu_seqlens=cu, q_pos=q_pos,
+                                dO=None if do_rows is None else do_rows.astype(np.float64))

@@ -1,0 +1,122 @@
+"""CPU-side checks of the boundary: the library loads, exports everything the header
+declares, lays out the zigzag shards exactly like the oracle, and rejects bad arguments with
+a status (nothing here launches a kernel)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import mmsp_oracle as orc
+from paper_2408_10188_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "mmsp.h")).read()
+    declared = set(re.findall(r"\b(mmsp_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B._lib, name), name
+
+
+@pytest.mark.parametrize("T,N", [(8, 4), (512, 2), (16384, 4), (65536, 8), (262144, 32), (96, 3)])
+def test_layout_and_plan_match_the_oracle_bit_for_bit(T, N):
+    for r in range(N):
+        ids, l2g = B.mmsp_zigzag_layout(T, N, r)
+        ids_o, l2g_o = orc.zigzag_layout(T, N, r)
+        assert list(ids) == ids_o.tolist()
+        assert l2g.dtype == np.int64 and np.array_equal(l2g, l2g_o)
+        for s in range(N):
+            src, blk = B.mmsp_zigzag_plan(T, N, r, s)
+            ref = orc.zigzag_plan(T, N, r, s)
+            got = dict(src=src, q_row0=blk.q_row0, n_q=blk.n_q, k_row0=blk.k_row0, n_k=blk.n_k,
+                       q_pos0=blk.q_pos0, k_pos0=blk.k_pos0, mask=blk.mask)
+            assert got == ref
+            assert blk.cu_seqlens is None and blk.n_docs == 0
+
+
+def test_layout_of_the_papers_example():
+    got = [B.mmsp_zigzag_layout(8, 4, r)[1].tolist() for r in range(4)]
+    assert got == [[0, 7], [1, 6], [2, 5], [3, 4]]
+
+
+@pytest.mark.parametrize("T,N,rank", [(10, 4, 0), (8, 0, 0), (8, 4, 4), (8, 4, -1), (0, 1, 0), (-8, 4, 0)])
+def test_layout_rejects_bad_arguments(T, N, rank):
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_zigzag_layout(T, N, rank)
+    assert e.value.status == B.MMSP_ERR_INVALID_ARG
+    assert B.mmsp_last_error() != ""
+
+
+def test_plan_rejects_bad_step():
+    for step in (-1, 4):
+        with pytest.raises(B.MmspError) as e:
+            B.mmsp_zigzag_plan(8, 4, 0, step)
+        assert e.value.status == B.MMSP_ERR_INVALID_ARG
+
+
+def _shape(**kw):
+    base = dict(n_q_heads=4, n_kv_heads=2, head_dim=128, io_dtype=B.MMSP_BF16, softmax_scale=0.1,
+                q_strides=(512, 128), kv_strides=(256, 128), lse_head_stride=64)
+    base.update(kw)
+    return B.make_shape(**base)
+
+
+FAKE = 0x1000  # a 16-byte aligned non-NULL value; never dereferenced because validation fails first
+
+
+@pytest.mark.parametrize("shape_kw,blk_kw,status", [
+    (dict(n_kv_heads=3), {}, B.MMSP_ERR_INVALID_ARG),
+    (dict(head_dim=96), {}, B.MMSP_ERR_UNSUPPORTED),
+    (dict(head_dim=64), {}, B.MMSP_ERR_UNSUPPORTED),               # bf16 needs 128
+    (dict(io_dtype=7), {}, B.MMSP_ERR_INVALID_ARG),
+    (dict(softmax_scale=0.0), {}, B.MMSP_ERR_INVALID_ARG),
+    (dict(softmax_scale=float("nan")), {}, B.MMSP_ERR_INVALID_ARG),
+    (dict(q_strides=(100, 128)), {}, B.MMSP_ERR_INVALID_ARG),
+    (dict(kv_strides=(256, 4)), {}, B.MMSP_ERR_INVALID_ARG),
+    ({}, dict(n_q=-1), B.MMSP_ERR_INVALID_ARG),
+    ({}, dict(q_row0=60, n_q=8), B.MMSP_ERR_INVALID_ARG),           # beyond lse_head_stride
+    ({}, dict(k_row0=-2), B.MMSP_ERR_INVALID_ARG),
+    ({}, dict(mask=5), B.MMSP_ERR_INVALID_ARG),
+    ({}, dict(n_docs=3), B.MMSP_ERR_INVALID_ARG),                   # n_docs without cu_seqlens
+    ({}, dict(q_pos0=1 << 40), B.MMSP_ERR_INVALID_ARG),
+])
+def test_step_calls_reject_bad_shapes_and_blocks(shape_kw, blk_kw, status):
+    shape = _shape(**shape_kw)
+    b = dict(q_row0=0, n_q=16, k_row0=0, n_k=16, mask=B.MMSP_MASK_FULL)
+    b.update(blk_kw)
+    blk = B.make_block(**b)
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_step_fwd(shape, blk, FAKE, FAKE, FAKE, FAKE, FAKE, 0)
+    assert e.value.status == status
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_step_bwd(shape, blk, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 0)
+    assert e.value.status == status
+
+
+def test_null_and_misaligned_pointers_are_rejected():
+    shape, blk = _shape(), B.make_block(0, 16, 0, 16, B.MMSP_MASK_FULL)
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_step_fwd(shape, blk, None, FAKE, FAKE, FAKE, FAKE, 0)
+    assert e.value.status == B.MMSP_ERR_INVALID_ARG
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_step_fwd(shape, blk, FAKE + 2, FAKE, FAKE, FAKE, FAKE, 0)
+    assert e.value.status == B.MMSP_ERR_INVALID_ARG
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_merge(shape, 0, 16, FAKE, FAKE, FAKE, None, None)
+    assert e.value.status == B.MMSP_ERR_INVALID_ARG
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_merge(shape, 0, 16, FAKE, FAKE, None, None, None)        # nothing to do
+    assert e.value.status == B.MMSP_ERR_INVALID_ARG
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_delta(shape, 0, 16, None, FAKE, FAKE)
+    assert e.value.status == B.MMSP_ERR_INVALID_ARG
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_step_bwd(shape, blk, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 1, FAKE, FAKE, FAKE, 0)
+    assert e.value.status == B.MMSP_ERR_INVALID_ARG                       # compute_delta without o_final
+
+
+def test_workspace_is_zero():
+    assert B.mmsp_workspace_bytes(_shape(), 8192, 8192, 1) == 0

@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of one rank's attention under MM-SP on one MI355X.
+
+A "step" is one pass of the whole hot path for one virtual rank of the zigzag ring:
+layout/plan (host), N forward ring steps with the LSE merge fused into the kernel epilogue,
+the cast of the final O, the delta pre-pass and N backward ring steps -- on synthetic,
+seeded inputs already resident in HBM.  Default workload: the 256K-token shard
+(28/4 heads, d 128, bf16, N 32, C 4096, T 262144), rank 0.
+
+Prints ONE JSON line: causal-adjusted TFLOP/s (4d flops per visible pair forward, 10d
+backward, pairs counted exactly), the roofline entry of the dominant kernel (timed with HIP
+events in an instrumented pass), and the fp64 oracle timed on the host cores on a bounded
+sample of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+BF16_DENSE_PEAK_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
+HBM_PEAK_GBS = 8000.0
+
+
+def pairs_of_rank(N, C):
+    """Visible (query, key) pairs per query head for any rank of the zigzag layout: 2NC^2 + C."""
+    return 2 * N * C * C + C
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="long", choices=["cfg3", "long"])
+    ap.add_argument("--rank", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=32, help="query rows per chunk in the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the ring (one rank); this build has no multi-GPU path: "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2408_10188_amd import binding as B
+    from paper_2408_10188_amd import ring, synth
+
+    cfg = synth.CONFIGS[args.config]
+    N, C, Hq, Hkv, d = cfg["N"], cfg["C"], cfg["Hq"], cfg["Hkv"], cfg["d"]
+    T, n = 2 * N * C, 2 * C
+    rank = args.rank
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    def upload(x):
+        return torch.from_numpy(synth.bf16_bits(x).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    # ---- synthetic inputs, chunk by chunk (the full K/V never sit on the host in fp32 at once)
+    k_zz = torch.empty(N, n, Hkv, d, dtype=torch.bfloat16, device=dev)
+    v_zz = torch.empty_like(k_zz)
+    for r in range(N):
+        for half, c in enumerate((r, 2 * N - 1 - r)):
+            k_zz[r, half * C:(half + 1) * C] = upload(synth.chunk("k", c, C, Hkv, d, cfg["sigma"], cfg["seed"]))
+            v_zz[r, half * C:(half + 1) * C] = upload(synth.chunk("v", c, C, Hkv, d, cfg["sigma"], cfg["seed"]))
+    chunks = (rank, 2 * N - 1 - rank)
+    q_host = np.concatenate([synth.chunk("q", c, C, Hq, d, cfg["sigma"], cfg["seed"]) for c in chunks])
+    do_host = np.concatenate([synth.chunk("do", c, C, Hq, d, 1.0, cfg["seed"]) for c in chunks])
+    q, d_o = upload(q_host), upload(do_host)
+
+    shape = ring.shape_for(q, k_zz, B.MMSP_BF16, n, 1.0 / math.sqrt(d))
+    o_acc = torch.empty(n, Hq, d, dtype=torch.float32, device=dev)
+    lse = torch.empty(Hq, n, dtype=torch.float32, device=dev)
+    o_final = torch.empty_like(q)
+    delta = torch.empty_like(lse)
+    dq = torch.zeros_like(o_acc)
+    dk_zz = torch.zeros(N, n, Hkv, d, dtype=torch.float32, device=dev)   # rows this rank never reaches stay 0
+    dv_zz = torch.zeros_like(dk_zz)
+
+    def one_pass():
+        ring.rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final)
+        dq.zero_()
+        ring.rank_backward(shape, T, N, rank, q, k_zz, v_zz, o_final, d_o, lse, delta, dq, dk_zz, dv_zz)
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_pass()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    pairs = pairs_of_rank(N, C)
+    flops_fwd = 4 * d * Hq * pairs
+    flops_bwd = 10 * d * Hq * pairs
+    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+
+    # ---- instrumented pass: HIP events around each kind of call (same stream the kernels run on)
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); fn(); e1.record()
+        return e0, e1
+
+    plans = [B.mmsp_zigzag_plan(T, N, rank, s) for s in range(N)]
+    kinds = {"fwd_step": [], "merge_cast": [], "delta": [], "bwd_dq": [], "bwd_dkdv": []}
+    for _ in range(2):
+        for s, (src, blk) in enumerate(plans):
+            kinds["fwd_step"].append((timed(lambda: B.mmsp_attn_step_fwd(shape, blk, q, k_zz[src], v_zz[src], o_acc, lse, s > 0)), blk))
+        kinds["merge_cast"].append((timed(lambda: B.mmsp_attn_merge(shape, 0, n, o_acc, lse, None, None, o_final)), None))
+        kinds["delta"].append((timed(lambda: B.mmsp_attn_delta(shape, 0, n, o_final, d_o, delta)), None))
+        dq.zero_()
+        for src, blk in plans:
+            kinds["bwd_dq"].append((timed(lambda: B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, 0, dq, None, None, 0)), blk))
+            kinds["bwd_dkdv"].append((timed(lambda: B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, 0, None, dk_zz[src], dv_zz[src], 0)), blk))
+    torch.cuda.synchronize()
+
+    def blk_pairs(blk):
+        if blk.mask == B.MMSP_MASK_CAUSAL_DIAG:
+            return blk.n_q * (blk.n_q + 1) // 2
+        return blk.n_q * blk.n_k
+
+    # algorithmic flops per visible pair and head of each kernel: forward S and PV (4d); the dK/dV
+    # kernel owns S, dP, dV, dK (8d); the dQ kernel owns dQ (2d) -- its S/dP recompute earns nothing
+    per_pair = {"fwd_step": 4 * d, "bwd_dq": 2 * d, "bwd_dkdv": 8 * d}
+    breakdown = {}
+    for name, lst in kinds.items():
+        ms = [e0.elapsed_time(e1) for (e0, e1), _ in lst]
+        entry = {"calls_per_pass": len(lst) // 2, "avg_ms": sum(ms) / len(ms), "total_ms_per_pass": sum(ms) / 2}
+        if name in per_pair:
+            fl = sum(per_pair[name] * Hq * blk_pairs(b) for _, b in lst) / len(lst)
+            entry["alg_tflops_per_launch"] = fl / 1e12
+            entry["tflops"] = fl / (entry["avg_ms"] * 1e-3) / 1e12
+        else:
+            elt = 2  # bf16 O / dO
+            byts = n * Hq * (d * (4 + elt) + 4) if name == "merge_cast" else n * Hq * (2 * d * elt + 4)
+            entry["alg_bytes_per_launch"] = byts
+            entry["gbs"] = byts / (entry["avg_ms"] * 1e-3) / 1e9
+        breakdown[name] = entry
+    dominant = max(per_pair, key=lambda k: breakdown[k]["total_ms_per_pass"])
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(dominant)
+        except Exception:
+            traffic = None
+    roofline = {"kernel": dominant, "bound": "mfma", "achieved": breakdown[dominant]["tflops"],
+                "peak": BF16_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": breakdown[dominant]["tflops"] / BF16_DENSE_PEAK_TFLOPS, "traffic": traffic,
+                "avg_launch_ms": breakdown[dominant]["avg_ms"]}
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import mmsp_oracle as orc
+        rows = np.concatenate([np.linspace(0, C - 1, args.cpu_rows).astype(np.int64),
+                               C + np.linspace(0, C - 1, args.cpu_rows).astype(np.int64)])
+        _, l2g = orc.zigzag_layout(T, N, rank)
+        K = np.empty((T, Hkv, d)); V = np.empty((T, Hkv, d))
+        for c in range(2 * N):
+            K[c * C:(c + 1) * C] = synth.chunk("k", c, C, Hkv, d, cfg["sigma"], cfg["seed"])
+            V[c * C:(c + 1) * C] = synth.chunk("v", c, C, Hkv, d, cfg["sigma"], cfg["seed"])
+        tc = time.perf_counter()
+        ref = orc.causal_attention(q_host[rows].astype(np.float64), K, V, 1.0 / math.sqrt(d), q_pos=l2g[rows],
+                                   dO=do_host[rows].astype(np.float64))
+        cpu_s = time.perf_counter() - tc
+        sample_pairs = int((l2g[rows] + 1).sum())
+        cpu_flops = 14 * d * Hq * sample_pairs
+        err_o = float(np.abs(o_acc[torch.from_numpy(rows).to(dev)].double().cpu().numpy() - ref[0]).max())
+        err_dq = float(np.abs(dq[torch.from_numpy(rows).to(dev)].double().cpu().numpy() - ref[2]).max())
+        cpu = {"value": cpu_flops / cpu_s / 1e12, "unit": "TFLOP/s", "cores": len(os.sched_getaffinity(0)),
+               "kind": "oracle", "seconds": cpu_s,
+               "sample": "%d query rows (%d per chunk, evenly spaced) of rank %d x all %d heads, fwd+bwd (dQ rows; "
+                         "dK/dV contribution of those rows), fp64 numpy; %.3e of the shard's pairs"
+                         % (len(rows), args.cpu_rows, rank, Hq, sample_pairs / pairs),
+               "gpu_vs_oracle_max_abs": {"o": err_o, "dq": err_dq}}
+
+    out = {
+        "metric": "causal attention TFLOP/s fwd+bwd per rank shard; % of MI355X bf16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "frac_of_bf16_dense_peak": value / BF16_DENSE_PEAK_TFLOPS,
+        "config": {"workload": "%s: zigzag rank %d of N=%d, C=%d (T=%d), %d/%d heads, d=%d, bf16, fwd+bwd over all %d "
+                               "ring steps" % (args.config, rank, N, C, T, Hq, Hkv, d, N),
+                   "pairs_per_head": pairs, "tflop_fwd": flops_fwd / 1e12, "tflop_bwd": flops_bwd / 1e12},
+        "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

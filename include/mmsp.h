@@ -149,6 +149,8 @@ mmsp_status mmsp_attn_delta(const mmsp_shape* shape, int64_t row0, int64_t n_row
  *   d_o (as mmsp_attn_delta) and stored in `delta`; otherwise o_final may be NULL.
  * dq_acc is always accumulated into (the caller zeroes it before the first step).
  * accumulate_dkdv == 0 overwrites dk/dv rows [k_row0, k_row0+n_k); != 0 adds to them.
+ * dq_acc may be NULL to skip dQ; dk and dv may both be NULL to skip dK/dV (in a ring the
+ * two travel differently: dQ stays with the rank, dK/dV follow the K/V block).
  * Results are bit-identical from run to run (no floating-point atomics). */
 mmsp_status mmsp_attn_step_bwd(const mmsp_shape* shape, const mmsp_block* blk,
                                const void* q, const void* k, const void* v,

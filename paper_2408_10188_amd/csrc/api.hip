@@ -210,9 +210,10 @@ mmsp_status mmsp_attn_step_bwd(const mmsp_shape* shape, const mmsp_block* blk, c
   if (st != MMSP_OK) return st;
   st = check_block(shape, blk);
   if (st != MMSP_OK) return st;
-  if (q == nullptr || k == nullptr || v == nullptr || d_o == nullptr || lse_final == nullptr || delta == nullptr ||
-      dq_acc == nullptr || dk == nullptr || dv == nullptr)
-    return fail(MMSP_ERR_INVALID_ARG, "q, k, v, d_o, lse_final, delta, dq_acc, dk and dv must be non-NULL");
+  if (q == nullptr || k == nullptr || v == nullptr || d_o == nullptr || lse_final == nullptr || delta == nullptr)
+    return fail(MMSP_ERR_INVALID_ARG, "q, k, v, d_o, lse_final and delta must be non-NULL");
+  if ((dk == nullptr) != (dv == nullptr)) return fail(MMSP_ERR_INVALID_ARG, "dk and dv must both be given or both be NULL");
+  if (dq_acc == nullptr && dk == nullptr) return fail(MMSP_ERR_INVALID_ARG, "nothing to do: dq_acc, dk and dv are all NULL");
   if (compute_delta && o_final == nullptr) return fail(MMSP_ERR_INVALID_ARG, "compute_delta needs o_final");
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(o_final) ||
       !aligned16(dq_acc) || !aligned16(dk) || !aligned16(dv))
@@ -225,7 +226,7 @@ mmsp_status mmsp_attn_step_bwd(const mmsp_shape* shape, const mmsp_block* blk, c
   }
   if (blk->n_k == 0) return MMSP_OK;
   if (blk->mask == MMSP_MASK_NONE || blk->n_q == 0) {
-    if (accumulate_dkdv) return MMSP_OK;
+    if (accumulate_dkdv || dk == nullptr) return MMSP_OK;
     const int64_t first = blk->k_row0 * shape->n_kv_heads * shape->head_dim;
     const int64_t count = blk->n_k * shape->n_kv_heads * shape->head_dim;
     hipError_t e = mmsp::launch_zero_f32(dk + first, count, stream);

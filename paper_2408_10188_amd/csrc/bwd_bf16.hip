@@ -77,6 +77,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_bf16_kernel(StepArgs a) {
     tile_load(kr, kbase, a.kv_ts, kt0 * kBN, a.n_k, tid);
     tile_load(vr, vbase, a.kv_ts, kt0 * kBN, a.n_k, tid);
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  /* vmcnt(0) */   // Q, dO, first tile landed: nothing stays pending across the back edge
   for (int kt = kt0; kt <= kt1; ++kt) {
     __syncthreads();                                   // every wavefront is done with the old tile
     tile_store_n(kr, ktile, tid);
@@ -212,6 +213,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a) {
     }
   };
   if (niter > 0) prefetch(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  /* vmcnt(0) */   // K, V, first tile landed (see the dq kernel)
 
   for (int it = 0; it < niter; ++it) {
     __syncthreads();
@@ -291,7 +293,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a) {
 }  // namespace
 
 hipError_t launch_bwd_bf16(const StepArgs& a, hipStream_t stream) {
-  {
+  if (a.dq != nullptr) {
     const dim3 g((a.n_q + kBM - 1) / kBM, a.Hq), b(256);
     const size_t smem = 3 * kTileBytes;
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_bf16_kernel),
@@ -301,7 +303,7 @@ hipError_t launch_bwd_bf16(const StepArgs& a, hipStream_t stream) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  {
+  if (a.dk != nullptr) {
     const dim3 g((a.n_k + kBM - 1) / kBM, a.Hkv), b(256);
     const size_t smem = 4 * kTileBytes + 128 * sizeof(float);
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkdv_bf16_kernel),

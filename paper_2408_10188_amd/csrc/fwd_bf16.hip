@@ -58,41 +58,68 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(StepArgs a) {
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
-  float m = -INFINITY;       // running max of the raw (unscaled) scores of this query
-  float l = 0.f;             // this lane's share of the running sum (its 32 of every 64 keys)
+  // Softmax state.  m_ref is the raw-score reference the exponentials are taken against; it
+  // follows the running row maximum lazily: it only moves when the maximum has grown by more
+  // than kLazy in the exponent (P stays <= 2^kLazy), so the O rescale is rare.
+  constexpr float kLazy = 8.f;
+  float m_ref = -INFINITY;
+  float neg_mc = 0.f;        // -m_ref * c  (0 while m_ref = -inf, so masked scores give exp2(-inf) = 0)
+  float l = 0.f;             // this lane's share of the row sum (its 32 of every 64 keys)
   const float c = a.scale * kLog2e;
+  const float lazy_raw = kLazy / c;
 
-  const uint16_t* kbase = reinterpret_cast<const uint16_t*>(a.k) + (int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs;
-  const uint16_t* vbase = reinterpret_cast<const uint16_t*>(a.v) + (int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs;
+  const char* kbase = reinterpret_cast<const char*>(a.k) + ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
+  const char* vbase = reinterpret_cast<const char*>(a.v) + ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
+  const int64_t tile_bytes = (int64_t)kBN * a.kv_ts * 2;
+  const TileOffs off_full = tile_offsets(a.kv_ts, kBN, tid);
+
+  // LDS read addresses, fixed for the whole call: K operand k-step ks (rows +32 -> +8192 bytes),
+  // V^T operand chunk pair x = g ^ db (d block db -> +4096 bytes)
+  int ka[8], va[4];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) ka[ks] = tile_n_offset(col, ks * 2 + half);
+#pragma unroll
+  for (int x = 0; x < 4; ++x) va[x] = kTileBytes + tile_t_offset(col, x * 2 + half);
 
   TileRegs kr, vr;
+  auto prefetch = [&](int kt) {
+    const int left = a.n_k - kt * kBN;
+    const char* kp = kbase + (int64_t)kt * tile_bytes;
+    const char* vp = vbase + (int64_t)kt * tile_bytes;
+    if (left >= kBN) {
+      tile_load(kr, kp, off_full);
+      tile_load(vr, vp, off_full);
+    } else {                         // ragged last tile: rows past the end repeat the last row (masked later)
+      const TileOffs off = tile_offsets(a.kv_ts, left, tid);
+      tile_load(kr, kp, off);
+      tile_load(vr, vp, off);
+    }
+  };
   if (kt0 <= kt1) {
-    tile_load(kr, kbase, a.kv_ts, kt0 * kBN, a.n_k, tid);
-    tile_load(vr, vbase, a.kv_ts, kt0 * kBN, a.n_k, tid);
+    prefetch(kt0);
     tile_store_n(kr, smem, tid);
     tile_store_t(vr, smem + kTileBytes, tid);
   }
+  // Every load issued so far (Q, first tile) must have landed before the loop: otherwise the
+  // compiler keeps them "pending" across the back edge and waits on the prefetch loads instead.
+  __builtin_amdgcn_s_waitcnt(0x0F70);  /* vmcnt(0) */
   __syncthreads();
 
-  int buf = 0;
-  for (int kt = kt0; kt <= kt1; ++kt) {
-    const char* ktile = smem + buf * 2 * kTileBytes;
-    const char* vtile = ktile + kTileBytes;
+  auto tile_body = [&](int kt, const char* cur, char* nxt) {
     const bool more = kt < kt1;
-    if (more) {
-      tile_load(kr, kbase, a.kv_ts, (kt + 1) * kBN, a.n_k, tid);
-      tile_load(vr, vbase, a.kv_ts, (kt + 1) * kBN, a.n_k, tid);
-    }
+    if (more) prefetch(kt + 1);
     const int k0 = kt * kBN;
 
-    // ---- S^T = K Q^T : two 32-key blocks ----
+    // ---- S^T = K Q^T : two 32-key blocks, their accumulation chains interleaved ----
     f32x16 s[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) s[kb] = mfma32(tile_n_read(ktile, kb, ks, lane), qreg[ks], s[kb]);
+    for (int ks = 0; ks < 8; ++ks) {
+      s[0] = mfma32(*reinterpret_cast<const u32x4*>(cur + ka[ks]), qreg[ks], s[0]);
+      s[1] = mfma32(*reinterpret_cast<const u32x4*>(cur + ka[ks] + 8192), qreg[ks], s[1]);
     }
 
     // ---- mask (only tiles that cut an interval boundary) ----
@@ -113,46 +140,56 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(StepArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m - m_use) * c);    // m = -inf -> 0
-    const float neg_mc = -m_use * c;
-    m = m_new;
-    float psum = 0.f;
-    u32x4 pb[4];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      float p[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        p[i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], c, neg_mc));
-        psum += p[i];
-      }
-      pb[kb * 2 + 0] = mk4(pack2(p[0], p[1]), pack2(p[2], p[3]), pack2(p[4], p[5]), pack2(p[6], p[7]));
-      pb[kb * 2 + 1] = mk4(pack2(p[8], p[9]), pack2(p[10], p[11]), pack2(p[12], p[13]), pack2(p[14], p[15]));
-    }
-    l = l * alpha + psum;
-    if (__any(alpha != 1.f)) {
+    if (__any(mx > m_ref + lazy_raw)) {                 // rare after the first tiles
+      const float m_new = fmaxf(m_ref, mx);
+      const float alpha = m_new == m_ref ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * c);   // -inf -> 0
+      m_ref = m_new;
+      neg_mc = m_new == -INFINITY ? 0.f : -m_new * c;
+      l *= alpha;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
     }
+    u32x4 pb[4];
+    float ps[4] = {0.f, 0.f, 0.f, 0.f};                 // fp32 sums of the unrounded P (LSE needs 1e-3)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      uint32_t w[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][2 * j], c, neg_mc));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][2 * j + 1], c, neg_mc));
+        ps[(2 * j) & 3] += p0;
+        ps[(2 * j + 1) & 3] += p1;
+        w[j] = pack2(p0, p1);
+      }
+      pb[kb * 2 + 0] = mk4(w[0], w[1], w[2], w[3]);
+      pb[kb * 2 + 1] = mk4(w[4], w[5], w[6], w[7]);
+    }
+    l += (ps[0] + ps[1]) + (ps[2] + ps[3]);
 
     // ---- O^T += V^T P^T ----
 #pragma unroll
     for (int g = 0; g < 4; ++g)
 #pragma unroll
-      for (int db = 0; db < 4; ++db) oacc[db] = mfma32(tile_t_read(vtile, db, g, lane), pb[g], oacc[db]);
+      for (int db = 0; db < 4; ++db)
+        oacc[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + va[g ^ db] + db * 4096), pb[g], oacc[db]);
 
     if (more) {
-      char* nk = smem + (buf ^ 1) * 2 * kTileBytes;
-      tile_store_n(kr, nk, tid);
-      tile_store_t(vr, nk + kTileBytes, tid);
+      tile_store_n(kr, nxt, tid);
+      tile_store_t(vr, nxt + kTileBytes, tid);
     }
     __syncthreads();
-    buf ^= 1;
+  };
+
+  char* buf0 = smem;
+  char* buf1 = smem + 2 * kTileBytes;
+  for (int kt = kt0; kt <= kt1; kt += 2) {              // two bodies so that LDS offsets are immediates
+    tile_body(kt, buf0, buf1);
+    if (kt + 1 <= kt1) tile_body(kt + 1, buf1, buf0);
   }
+  const float m = m_ref;
 
   // ---- epilogue ----
   l += __shfl_xor(l, 32);

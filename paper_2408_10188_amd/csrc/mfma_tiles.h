@@ -33,6 +33,11 @@ __device__ __forceinline__ u32x4 mk4(uint32_t a, uint32_t b, uint32_t c, uint32_
   return r;
 }
 
+// acc + lo + hi of a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1))
+__device__ __forceinline__ float add_pair(uint32_t packed, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
+}
+
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   f32x2 x = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
@@ -56,12 +61,15 @@ __device__ __forceinline__ u32x4 tile_n_read(const char* tile, int rb, int ks, i
 }
 
 // ---------------------------------------------------------------------------------------
-// TileT: the same 64x128 tile transposed, [128 d][64 token slots], 128 bytes per row.  Token
-// t of the tile sits in slot (t & ~15) | swap_bits_2_3(t & 15), which is the k-slot order
-// described above; 16-byte chunks are XOR-swizzled by (d >> 1) & 7.
+// TileT: the same 64x128 tile transposed, [128 d][64 token slots].  Token t of the tile sits
+// in slot (t & ~15) | swap_bits_2_3(t & 15), which is the k-slot order described above.
+// Rows 2j and 2j+1 share one 256-byte bank line; which half a row takes is flipped by bit 3
+// of d, and the 16-byte chunks inside the half are XOR-swizzled by (d >> 4) ^ (d >> 1).  With
+// this placement both the b128 operand reads (32 consecutive d, one chunk) and the b64
+// transposing writes (d = 8 * lane + e, see tile_store_t) touch every bank equally often.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int tile_t_offset(int d, int chunk /*0..7*/) {
-  return d * 128 + ((chunk ^ ((d >> 1) & 7)) << 4);
+  return (d >> 1) * 256 + (((d ^ (d >> 3)) & 1) << 7) + (((chunk ^ (d >> 4) ^ (d >> 1)) & 7) << 4);
 }
 // A operand for d rows [db*32, db*32+32), k-step g (tokens 16g .. 16g+16 in permuted order)
 __device__ __forceinline__ u32x4 tile_t_read(const char* tile, int db, int g, int lane) {
@@ -69,16 +77,22 @@ __device__ __forceinline__ u32x4 tile_t_read(const char* tile, int db, int g, in
   return *reinterpret_cast<const u32x4*>(tile + tile_t_offset(d, g * 2 + (lane >> 5)));
 }
 
-// Staging registers for one 64x128 tile and 256 threads: thread t owns tokens
-// 4*(t/16) .. +4 and d-chunk (t%16)*8 .. +8  ->  four 16-byte global loads, each row of the
-// tile being read by 16 consecutive lanes (256 contiguous bytes).
+// Staging registers for one 64x128 tile and 256 threads: thread t owns the token group
+// kg = stage_kg(t) (tokens 4kg .. 4kg+3) and d-chunk (t%16)*8 .. +8  ->  four 16-byte global
+// loads, each row of the tile being read by 16 consecutive lanes (256 contiguous bytes).
+// Within a wavefront the 16-lane groups take token groups 0, 2, 1, 3 so that the first 32
+// lanes of a transposing b64 write differ in the 8-byte half of a chunk, not in the chunk.
 struct TileRegs { u32x4 r[4]; };
+
+__device__ __forceinline__ int stage_kg(int tid) {
+  return (tid >> 6) * 4 + ((tid >> 4) & 1) * 2 + ((tid >> 5) & 1);
+}
 
 // rows are clamped to [0, n_rows-1] so that every load is in bounds; clamped duplicates are
 // masked (or never stored) by the caller.
 __device__ __forceinline__ void tile_load(TileRegs& t, const uint16_t* base, int64_t row_stride, int row0, int n_rows,
                                           int tid) {
-  const int tok = (tid >> 4) * 4, dc = tid & 15;
+  const int tok = stage_kg(tid) * 4, dc = tid & 15;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int row = min(row0 + tok + r, n_rows - 1);
@@ -86,8 +100,26 @@ __device__ __forceinline__ void tile_load(TileRegs& t, const uint16_t* base, int
   }
 }
 
+// Same loads with the addressing split into a wavefront-uniform tile pointer and per-lane
+// 32-bit byte offsets that do not change from tile to tile (no per-tile address arithmetic).
+struct TileOffs { uint32_t o[4]; };
+
+__device__ __forceinline__ TileOffs tile_offsets(int64_t row_stride, int rows_left /* clamp: rows >= this repeat the last */,
+                                                 int tid) {
+  const int tok = stage_kg(tid) * 4, dc = tid & 15;
+  TileOffs t;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) t.o[r] = (uint32_t)(min(tok + r, rows_left - 1) * (int)row_stride * 2 + dc * 16);
+  return t;
+}
+
+__device__ __forceinline__ void tile_load(TileRegs& t, const char* tile_ptr /* uniform */, const TileOffs& off) {
+#pragma unroll
+  for (int r = 0; r < 4; ++r) t.r[r] = *reinterpret_cast<const u32x4*>(tile_ptr + off.o[r]);
+}
+
 __device__ __forceinline__ void tile_store_n(const TileRegs& t, char* tile, int tid) {
-  const int tok = (tid >> 4) * 4, dc = tid & 15;
+  const int tok = stage_kg(tid) * 4, dc = tid & 15;
 #pragma unroll
   for (int r = 0; r < 4; ++r) *reinterpret_cast<u32x4*>(tile + tile_n_offset(tok + r, dc)) = t.r[r];
 }
@@ -95,7 +127,7 @@ __device__ __forceinline__ void tile_store_n(const TileRegs& t, char* tile, int 
 __device__ __forceinline__ uint32_t comp(const u32x4& v, int i) { return v[i]; }   // i constant after unrolling
 
 __device__ __forceinline__ void tile_store_t(const TileRegs& t, char* tile, int tid) {
-  const int kg = tid >> 4, dc = tid & 15;
+  const int kg = stage_kg(tid), dc = tid & 15;
   // tokens 4kg..4kg+3: 16-group g16 = kg/4, offset bits (b3,b2) = ((kg%4)>>1, (kg%4)&1);
   // slot = b2*8 + b3*4 + (0..3)  ->  chunk = g16*2 + b2, byte offset inside the chunk = b3*8
   const int chunk = (kg >> 2) * 2 + (kg & 1);

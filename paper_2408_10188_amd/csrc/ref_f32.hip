@@ -171,11 +171,11 @@ hipError_t launch_fwd_f32(const StepArgs& a, hipStream_t stream) {
 hipError_t launch_bwd_f32(const StepArgs& a, hipStream_t stream) {
   const dim3 gq((a.n_q + 63) / 64, a.Hq), gk((a.n_k + 63) / 64, a.Hkv), b(64);
   if (a.d == 64) {
-    bwd_dq_f32_kernel<64><<<gq, b, 0, stream>>>(a);
-    bwd_dkdv_f32_kernel<64><<<gk, b, 0, stream>>>(a);
+    if (a.dq != nullptr) bwd_dq_f32_kernel<64><<<gq, b, 0, stream>>>(a);
+    if (a.dk != nullptr) bwd_dkdv_f32_kernel<64><<<gk, b, 0, stream>>>(a);
   } else {
-    bwd_dq_f32_kernel<128><<<gq, b, 0, stream>>>(a);
-    bwd_dkdv_f32_kernel<128><<<gk, b, 0, stream>>>(a);
+    if (a.dq != nullptr) bwd_dq_f32_kernel<128><<<gq, b, 0, stream>>>(a);
+    if (a.dk != nullptr) bwd_dkdv_f32_kernel<128><<<gk, b, 0, stream>>>(a);
   }
   return hipGetLastError();
 }

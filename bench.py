@@ -82,10 +82,14 @@ def main():
     dk_zz = torch.zeros(N, n, Hkv, d, dtype=torch.float32, device=dev)   # rows this rank never reaches stay 0
     dv_zz = torch.zeros_like(dk_zz)
 
+    ws_bytes = ring.workspace_bytes(shape, n, n)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
     def one_pass():
-        ring.rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final)
+        ring.rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes)
         dq.zero_()
-        ring.rank_backward(shape, T, N, rank, q, k_zz, v_zz, o_final, d_o, lse, delta, dq, dk_zz, dv_zz)
+        ring.rank_backward(shape, T, N, rank, q, k_zz, v_zz, o_final, d_o, lse, delta, dq, dk_zz, dv_zz, ws=ws,
+                           ws_bytes=ws_bytes)
 
     for _ in range(args.warmup):
         one_pass()
@@ -112,13 +116,13 @@ def main():
     kinds = {"fwd_step": [], "merge_cast": [], "delta": [], "bwd_dq": [], "bwd_dkdv": []}
     for _ in range(2):
         for s, (src, blk) in enumerate(plans):
-            kinds["fwd_step"].append((timed(lambda: B.mmsp_attn_step_fwd(shape, blk, q, k_zz[src], v_zz[src], o_acc, lse, s > 0)), blk))
+            kinds["fwd_step"].append((timed(lambda: B.mmsp_attn_step_fwd(shape, blk, q, k_zz[src], v_zz[src], o_acc, lse, s > 0, ws, ws_bytes)), blk))
         kinds["merge_cast"].append((timed(lambda: B.mmsp_attn_merge(shape, 0, n, o_acc, lse, None, None, o_final)), None))
         kinds["delta"].append((timed(lambda: B.mmsp_attn_delta(shape, 0, n, o_final, d_o, delta)), None))
         dq.zero_()
         for src, blk in plans:
-            kinds["bwd_dq"].append((timed(lambda: B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, 0, dq, None, None, 0)), blk))
-            kinds["bwd_dkdv"].append((timed(lambda: B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, 0, None, dk_zz[src], dv_zz[src], 0)), blk))
+            kinds["bwd_dq"].append((timed(lambda: B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, 0, dq, None, None, 0, ws, ws_bytes)), blk))
+            kinds["bwd_dkdv"].append((timed(lambda: B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, 0, None, dk_zz[src], dv_zz[src], 0, ws, ws_bytes)), blk))
     torch.cuda.synchronize()
 
     def blk_pairs(blk):

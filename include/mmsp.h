@@ -102,9 +102,12 @@ mmsp_status mmsp_zigzag_layout(int64_t T, int32_t N, int32_t rank,
 mmsp_status mmsp_zigzag_plan(int64_t T, int32_t N, int32_t rank, int32_t step,
                              int32_t* src_rank, mmsp_block* blk);
 
-/* Bytes of device workspace the step calls need for these extents (currently 0: the
- * kernels keep all intermediate state in registers and LDS).  `backward` != 0 asks for
- * mmsp_attn_step_bwd. */
+/* Bytes of device workspace the step calls need for blocks of at most n_q_max x n_k_max rows
+ * (0 for f32).  The bf16 kernels use it for token-contiguous (transposed) copies of tiles that
+ * each call rebuilds before its main kernel; nothing in it outlives a call.  `backward` != 0
+ * asks for mmsp_attn_step_bwd.  The workspace must be 16-byte aligned; a call given less
+ * returns MMSP_ERR_WORKSPACE_TOO_SMALL.  Two calls that may overlap in time (different
+ * streams) need separate workspaces. */
 size_t mmsp_workspace_bytes(const mmsp_shape* shape, int64_t n_q_max, int64_t n_k_max, int backward);
 
 /* One ring step, forward (the "local attention computation within each SP group rank" of
@@ -116,7 +119,7 @@ size_t mmsp_workspace_bytes(const mmsp_shape* shape, int64_t n_q_max, int64_t n_
  *   partial is applied in the kernel's epilogue (same arithmetic as mmsp_attn_merge).
  * Rows outside [q_row0, q_row0+n_q) are not touched.  A row that sees nothing gets
  * O_part = 0, LSE_part = -inf (and leaves a running result unchanged).
- * workspace may be NULL when mmsp_workspace_bytes() is 0. */
+ * workspace: at least mmsp_workspace_bytes(shape, n_q, n_k, 0) bytes (may be NULL when 0). */
 mmsp_status mmsp_attn_step_fwd(const mmsp_shape* shape, const mmsp_block* blk,
                                const void* q, const void* k, const void* v,
                                float* o, float* lse, int accumulate,

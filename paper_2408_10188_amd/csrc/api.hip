@@ -41,6 +41,8 @@ mmsp_status check_shape(const mmsp_shape* s) {
   if (s->q_tok_stride < d || s->q_head_stride < d || s->kv_tok_stride < d || s->kv_head_stride < d ||
       s->q_tok_stride % 8 || s->q_head_stride % 8 || s->kv_tok_stride % 8 || s->kv_head_stride % 8)
     return fail(MMSP_ERR_INVALID_ARG, "Q/KV strides must be >= head_dim and multiples of 8 elements");
+  if (s->q_tok_stride > (1 << 23) || s->kv_tok_stride > (1 << 23))
+    return fail(MMSP_ERR_INVALID_ARG, "token strides above 2^23 elements are not supported");
   if (s->lse_head_stride < 0) return fail(MMSP_ERR_INVALID_ARG, "lse_head_stride is negative");
   return MMSP_OK;
 }
@@ -86,6 +88,23 @@ mmsp::StepArgs make_args(const mmsp_shape* s, const mmsp_block* b) {
 mmsp_status device_result(hipError_t e, const char* what) {
   if (e == hipSuccess) return MMSP_OK;
   return fail(MMSP_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+// bf16 kernels read token-contiguous operands from pre-transposed tile images (16 KiB per 64
+// rows and head) that each call builds in the workspace: V^T for the forward.
+size_t needed_workspace(const mmsp_shape* s, int64_t n_q, int64_t n_k, bool backward) {
+  (void)n_q; (void)backward;
+  return (size_t)(s->n_kv_heads * mmsp::tiles_of(n_k) * mmsp::kImageBytes);
+}
+
+mmsp_status check_workspace(const mmsp_shape* s, const mmsp_block* b, bool backward, const void* ws, size_t ws_bytes) {
+  if (s->io_dtype != MMSP_BF16) return MMSP_OK;
+  const size_t need = needed_workspace(s, b->n_q, b->n_k, backward);
+  if (need == 0) return MMSP_OK;
+  if (ws == nullptr || ws_bytes < need)
+    return fail(MMSP_ERR_WORKSPACE_TOO_SMALL, "workspace of %zu bytes given, %zu needed (mmsp_workspace_bytes)", ws_bytes, need);
+  if (!aligned16(ws)) return fail(MMSP_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+  return MMSP_OK;
 }
 
 mmsp_status check_zigzag(int64_t T, int32_t N, int32_t rank) {
@@ -137,14 +156,13 @@ mmsp_status mmsp_zigzag_plan(int64_t T, int32_t N, int32_t rank, int32_t step, i
 }
 
 size_t mmsp_workspace_bytes(const mmsp_shape* shape, int64_t n_q_max, int64_t n_k_max, int backward) {
-  (void)shape; (void)n_q_max; (void)n_k_max; (void)backward;
-  return 0;
+  if (shape == nullptr || shape->io_dtype != MMSP_BF16 || n_q_max < 0 || n_k_max < 0) return 0;
+  return needed_workspace(shape, n_q_max, n_k_max, backward != 0);
 }
 
 mmsp_status mmsp_attn_step_fwd(const mmsp_shape* shape, const mmsp_block* blk, const void* q, const void* k,
                                const void* v, float* o, float* lse, int accumulate, void* workspace,
                                size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   mmsp_status st = check_shape(shape);
   if (st != MMSP_OK) return st;
   st = check_block(shape, blk);
@@ -155,6 +173,10 @@ mmsp_status mmsp_attn_step_fwd(const mmsp_shape* shape, const mmsp_block* blk, c
     return fail(MMSP_ERR_INVALID_ARG, "q, k, v and o must be 16-byte aligned");
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   if (blk->n_q == 0) return MMSP_OK;
+  if (blk->mask != MMSP_MASK_NONE && blk->n_k > 0) {
+    st = check_workspace(shape, blk, false, workspace, workspace_bytes);
+    if (st != MMSP_OK) return st;
+  }
   if (blk->mask == MMSP_MASK_NONE || blk->n_k == 0) {
     if (accumulate) return MMSP_OK;
     return device_result(mmsp::launch_fill_empty(o, lse, shape->lse_head_stride, shape->n_q_heads, shape->head_dim,
@@ -163,6 +185,7 @@ mmsp_status mmsp_attn_step_fwd(const mmsp_shape* shape, const mmsp_block* blk, c
   }
   mmsp::StepArgs a = make_args(shape, blk);
   a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse; a.accumulate = accumulate != 0;
+  a.ws = reinterpret_cast<char*>(workspace);
   if (shape->io_dtype == MMSP_BF16) return device_result(mmsp::launch_fwd_bf16(a, stream), "step_fwd (bf16)");
   return device_result(mmsp::launch_fwd_f32(a, stream), "step_fwd (f32)");
 }

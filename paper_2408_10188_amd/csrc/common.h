@@ -28,7 +28,11 @@ struct StepArgs {
   int32_t mask;                 // 0 full, 1 causal-diag
   int32_t n_docs;
   int32_t accumulate;           // fwd: merge into running state; bwd: add to dk/dv
+  char* ws;                     // caller's workspace (bf16 kernels)
 };
+
+constexpr int64_t kImageBytes = 16384;                       // one transposed 64x128 bf16 tile
+__host__ __device__ inline int64_t tiles_of(int64_t rows) { return (rows + 63) / 64; }
 
 // Visible key interval [lo, hi] (indices inside the block's key range, already clipped to
 // [0, n_k-1]) of the query row with block-relative index i.  Empty when lo > hi.
@@ -80,6 +84,11 @@ hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const
                         int row0, int n_rows, hipStream_t stream);
 hipError_t launch_delta(const void* o_final, const void* d_o, float* delta, int io_dtype,
                         int64_t lse_hs, int Hq, int d, int row0, int n_rows, hipStream_t stream);
+
+// Builds, for every 64-row tile and head of a [rows, H, 128] bf16 tensor, the 16 KiB image of
+// the transposed LDS tile (TileT) in `out` at ((head * n_tiles + tile) * 16384).
+hipError_t launch_transpose_tiles(const void* x, int64_t tok_stride, int64_t head_stride, int H, int row0, int n_rows,
+                                  void* out, hipStream_t stream);
 
 hipError_t launch_fwd_f32(const StepArgs& a, hipStream_t stream);
 hipError_t launch_bwd_f32(const StepArgs& a, hipStream_t stream);

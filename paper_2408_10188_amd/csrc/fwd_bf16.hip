@@ -1,9 +1,12 @@
 // Forward ring step on bf16 matrix cores, head_dim 128.
 //
-// Workgroup = 4 wavefronts = 128 query rows of one head; wavefront w owns 32 rows and keeps
-// their Q (as MFMA B operands, 32 VGPRs), O^T accumulator (128 d x 32 queries, 64 VGPRs) and
-// softmax statistics in registers for the whole call.  K/V stream through LDS in 64-key
-// tiles, double buffered, fetched from HBM/L2 into registers one tile ahead.
+// Workgroup = 8 wavefronts = 256 query rows of one head (two wavefronts per SIMD, so one
+// wavefront's softmax arithmetic overlaps the other's matrix work).  Wavefront w owns 32 rows
+// and keeps their Q (MFMA B operands, 32 VGPRs), the O^T accumulator (128 d x 32 queries, 64
+// VGPRs) and the softmax statistics in registers for the whole call.  K and V^T tiles of 64
+// keys stream through a three-stage LDS ring filled by asynchronous global->LDS copies: K
+// straight from the caller's tensor (swizzled by permuting which chunk a lane fetches), V^T
+// from the pre-transposed tile images in the workspace.
 //   S^T[key][query] = K . Q^T            (A = K tile from LDS, B = Q registers)
 //   online softmax down the key axis, which is in-lane in S^T's register layout
 //   O^T[d][query]  += V^T . P^T          (A = V^T tile from LDS, B = P^T straight from registers)
@@ -14,17 +17,41 @@
 namespace mmsp {
 namespace {
 
-constexpr int kBM = 128;   // query rows per workgroup
-constexpr int kBN = 64;    // keys per tile
+constexpr int kWaves = 8;
+constexpr int kBM = 32 * kWaves;   // query rows per workgroup
+constexpr int kBN = 64;            // keys per tile
+constexpr int kCopies = 16 / kWaves;
+constexpr int kStageBytes = 2 * kTileBytes;
+
+// vmcnt(n) with expcnt / lgkmcnt left alone
+__device__ __forceinline__ void wait_vmcnt_0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+__device__ __forceinline__ void wait_vmcnt_tile() { __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * kCopies)); }
 
 template <bool kAccum>
-__global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(StepArgs a) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];   // [2][K TileN | V TileT]
+__global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, int n_qt, int xcd_per_kv) {
+  __shared__ __attribute__((aligned(1024))) char stage0[kStageBytes];   // K TileN | V^T TileT
+  __shared__ __attribute__((aligned(1024))) char stage1[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char stage2[kStageBytes];
+
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, col = lane & 31;
-  // heaviest (latest) query tiles first: under the causal mask they have the most keys
-  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;
-  const int h = blockIdx.y, kvh = h / a.group;
+
+  // Workgroup -> (head, query tile).  Workgroups are dealt round-robin to the 8 XCDs; the
+  // ones that land on the same XCD work on the same KV head so its K/V block stays in that
+  // XCD's L2.  Later (heavier under the causal mask) query tiles go first.
+  int h, qt;
+  if (xcd_per_kv > 0) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int kvh0 = xcd / xcd_per_kv;
+    const int item = slot * xcd_per_kv + (xcd % xcd_per_kv);
+    if (item >= a.group * n_qt) return;
+    h = kvh0 * a.group + item % a.group;
+    qt = n_qt - 1 - item / a.group;
+  } else {
+    h = blockIdx.x % a.Hq;
+    qt = n_qt - 1 - blockIdx.x / a.Hq;
+  }
+  const int kvh = h / a.group;
   const int tile_row0 = qt * kBM;
   const int row = tile_row0 + wave * 32 + col;          // block-relative query row of this lane
   const bool live = row < a.n_q;
@@ -43,6 +70,21 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(StepArgs a) {
     key_interval_of_row(a, wr1, w_lo_max, dummy);
   }
   const int kt0 = t_lo / kBN, kt1 = t_hi >= t_lo ? t_hi / kBN : kt0 - 1;   // inclusive tile range
+
+  // ---- asynchronous tile fetch ----
+  const char* kbase = reinterpret_cast<const char*>(a.k) + ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
+  const char* vimg = a.ws + (int64_t)kvh * tiles_of(a.n_k) * kImageBytes;
+  const int64_t tile_bytes = (int64_t)kBN * a.kv_ts * 2;
+  const DmaOffs<kCopies> off_full = dma_n_offsets<kCopies>(a.kv_ts, kBN, wave, lane);
+  auto fetch = [&](int kt, char* stage) {
+    const int left = a.n_k - kt * kBN;
+    const char* kp = kbase + (int64_t)kt * tile_bytes;
+    if (left >= kBN) dma_tile_n<kCopies>(kp, off_full, stage, wave);
+    else dma_tile_n<kCopies>(kp, dma_n_offsets<kCopies>(a.kv_ts, left, wave, lane), stage, wave);   // ragged last tile
+    dma_tile_image<kCopies>(vimg + (int64_t)kt * kImageBytes, stage + kTileBytes, wave, lane);
+  };
+  if (kt0 <= kt1) fetch(kt0, stage0);
+  if (kt0 + 1 <= kt1) fetch(kt0 + 1, stage1);
 
   // Q as B operands: k-step ks covers d = ks*16 .. +16, this lane holds 8 of them
   u32x4 qreg[8];
@@ -68,49 +110,32 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(StepArgs a) {
   const float c = a.scale * kLog2e;
   const float lazy_raw = kLazy / c;
 
-  const char* kbase = reinterpret_cast<const char*>(a.k) + ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
-  const char* vbase = reinterpret_cast<const char*>(a.v) + ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
-  const int64_t tile_bytes = (int64_t)kBN * a.kv_ts * 2;
-  const TileOffs off_full = tile_offsets(a.kv_ts, kBN, tid);
-
-  // LDS read addresses, fixed for the whole call: K operand k-step ks (rows +32 -> +8192 bytes),
-  // V^T operand chunk pair x = g ^ db (d block db -> +4096 bytes)
+  // LDS read offsets inside a stage, fixed for the whole call: K operand k-step ks (rows +32 ->
+  // +8192 bytes), V^T operand chunk pair x = g ^ db (d block db -> +4096 bytes)
   int ka[8], va[4];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) ka[ks] = tile_n_offset(col, ks * 2 + half);
 #pragma unroll
   for (int x = 0; x < 4; ++x) va[x] = kTileBytes + tile_t_offset(col, x * 2 + half);
 
-  TileRegs kr, vr;
-  auto prefetch = [&](int kt) {
-    const int left = a.n_k - kt * kBN;
-    const char* kp = kbase + (int64_t)kt * tile_bytes;
-    const char* vp = vbase + (int64_t)kt * tile_bytes;
-    if (left >= kBN) {
-      tile_load(kr, kp, off_full);
-      tile_load(vr, vp, off_full);
-    } else {                         // ragged last tile: rows past the end repeat the last row (masked later)
-      const TileOffs off = tile_offsets(a.kv_ts, left, tid);
-      tile_load(kr, kp, off);
-      tile_load(vr, vp, off);
-    }
-  };
-  if (kt0 <= kt1) {
-    prefetch(kt0);
-    tile_store_n(kr, smem, tid);
-    tile_store_t(vr, smem + kTileBytes, tid);
-  }
-  // Every load issued so far (Q, first tile) must have landed before the loop: otherwise the
-  // compiler keeps them "pending" across the back edge and waits on the prefetch loads instead.
-  __builtin_amdgcn_s_waitcnt(0x0F70);  /* vmcnt(0) */
-  __syncthreads();
-
-  auto tile_body = [&](int kt, const char* cur, char* nxt) {
-    const bool more = kt < kt1;
-    if (more) prefetch(kt + 1);
+  auto tile_body = [&](int kt, const char* cur, char* refill) {
+    // Own copies of tile kt have landed (the newest tile's may still be in flight); after the
+    // barrier everybody's have, and everybody is done with the stage about to be refilled.
+    if (kt < kt1) wait_vmcnt_tile(); else wait_vmcnt_0();
+    lds_barrier();
+    if (kt + 2 <= kt1) fetch(kt + 2, refill);
     const int k0 = kt * kBN;
 
-    // ---- S^T = K Q^T : two 32-key blocks, their accumulation chains interleaved ----
+    // ---- S^T = K Q^T : two 32-key blocks, their accumulation chains interleaved.  All 16
+    // operand reads are issued up front so the MFMAs stream behind the LDS instead of waiting
+    // for it pair by pair. ----
+    u32x4 kop[16];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      kop[2 * ks] = *reinterpret_cast<const u32x4*>(cur + ka[ks]);
+      kop[2 * ks + 1] = *reinterpret_cast<const u32x4*>(cur + ka[ks] + 8192);
+    }
+    __builtin_amdgcn_sched_barrier(0);
     f32x16 s[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -118,9 +143,16 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(StepArgs a) {
       for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      s[0] = mfma32(*reinterpret_cast<const u32x4*>(cur + ka[ks]), qreg[ks], s[0]);
-      s[1] = mfma32(*reinterpret_cast<const u32x4*>(cur + ka[ks] + 8192), qreg[ks], s[1]);
+      s[0] = mfma32(kop[2 * ks], qreg[ks], s[0]);
+      s[1] = mfma32(kop[2 * ks + 1], qreg[ks], s[1]);
     }
+    // V^T operands for the second product: issued now, they land while the softmax runs
+    u32x4 vop[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int db = 0; db < 4; ++db) vop[g * 4 + db] = *reinterpret_cast<const u32x4*>(cur + va[g ^ db] + db * 4096);
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- mask (only tiles that cut an interval boundary) ----
     if (k0 < w_lo_max || k0 + kBN - 1 > w_hi_min) {
@@ -174,20 +206,14 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(StepArgs a) {
     for (int g = 0; g < 4; ++g)
 #pragma unroll
       for (int db = 0; db < 4; ++db)
-        oacc[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + va[g ^ db] + db * 4096), pb[g], oacc[db]);
-
-    if (more) {
-      tile_store_n(kr, nxt, tid);
-      tile_store_t(vr, nxt + kTileBytes, tid);
-    }
-    __syncthreads();
+        oacc[db] = mfma32(vop[g * 4 + db], pb[g], oacc[db]);
   };
 
-  char* buf0 = smem;
-  char* buf1 = smem + 2 * kTileBytes;
-  for (int kt = kt0; kt <= kt1; kt += 2) {              // two bodies so that LDS offsets are immediates
-    tile_body(kt, buf0, buf1);
-    if (kt + 1 <= kt1) tile_body(kt + 1, buf1, buf0);
+  // Three bodies per trip so that every LDS offset is an immediate.
+  for (int kt = kt0; kt <= kt1; kt += 3) {
+    tile_body(kt, stage0, stage2);
+    if (kt + 1 <= kt1) tile_body(kt + 1, stage1, stage0);
+    if (kt + 2 <= kt1) tile_body(kt + 2, stage2, stage1);
   }
   const float m = m_ref;
 
@@ -230,20 +256,21 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(StepArgs a) {
 
 }  // namespace
 
+int64_t fwd_bf16_workspace_bytes(int Hkv, int64_t n_k) { return (int64_t)Hkv * tiles_of(n_k) * kImageBytes; }
+
 hipError_t launch_fwd_bf16(const StepArgs& a, hipStream_t stream) {
-  const dim3 g((a.n_q + kBM - 1) / kBM, a.Hq), b(256);
-  const size_t smem = 4 * kTileBytes;   // two buffers of (K, V^T)
-  if (a.accumulate) {
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_bf16_kernel<true>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (attr != hipSuccess) return attr;
-    fwd_bf16_kernel<true><<<g, b, smem, stream>>>(a);
-  } else {
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_bf16_kernel<false>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (attr != hipSuccess) return attr;
-    fwd_bf16_kernel<false><<<g, b, smem, stream>>>(a);
+  // V^T tile images of the visiting block
+  hipError_t e = launch_transpose_tiles(a.v, a.kv_ts, a.kv_hs, a.Hkv, a.k_row0, a.n_k, a.ws, stream);
+  if (e != hipSuccess) return e;
+  const int n_qt = (a.n_q + kBM - 1) / kBM;
+  int xcd_per_kv = 0, n_blocks = n_qt * a.Hq;
+  if (8 % a.Hkv == 0) {
+    xcd_per_kv = 8 / a.Hkv;
+    n_blocks = 8 * ((a.group * n_qt + xcd_per_kv - 1) / xcd_per_kv);
   }
+  const dim3 g(n_blocks), b(64 * kWaves);
+  if (a.accumulate) fwd_bf16_kernel<true><<<g, b, 0, stream>>>(a, n_qt, xcd_per_kv);
+  else fwd_bf16_kernel<false><<<g, b, 0, stream>>>(a, n_qt, xcd_per_kv);
   return hipGetLastError();
 }
 

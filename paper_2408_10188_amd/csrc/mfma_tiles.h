@@ -148,4 +148,63 @@ __device__ __forceinline__ void tile_store_t(const TileRegs& t, char* tile, int 
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Asynchronous global -> LDS copies (global_load_lds_dwordx4): every lane supplies its own
+// global address; the 64 x 16 bytes of a wavefront land contiguously at a wavefront-uniform LDS
+// address.  Completion is tracked by vmcnt.  A swizzled LDS layout is obtained by permuting
+// which global chunk each lane fetches.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void dma16(const char* gptr, char* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+// Bare workgroup barrier for the asynchronous-copy pipelines.  __syncthreads() (and any
+// workgroup fence) makes the compiler wait for every outstanding vmcnt operation, including
+// the tile copies that are deliberately still in flight.  Here the copies a stage needs are
+// awaited explicitly (s_waitcnt vmcnt(n)) before the barrier, every LDS read of the stage being
+// recycled has been consumed by an MFMA issued before it, and the empty asm statements keep
+// the compiler from moving memory accesses across it.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// TileN by DMA: the tile is 16 wavefront-copies of 4 rows; copy j of a wavefront lands rows
+// 4j .. 4j+3.  Lane l of copy j fetches logical chunk (l % 16) ^ (row & 15) of row 4j + l/16.
+// kCopies = 16 / (wavefronts sharing the tile); the wavefront with index w takes copies
+// w, w + W, ...  Offsets are bytes from the tile's first row and fit 32 bits.
+template <int kCopies>
+struct DmaOffs { uint32_t o[kCopies]; };
+
+template <int kCopies>
+__device__ __forceinline__ DmaOffs<kCopies> dma_n_offsets(int64_t row_stride_elems, int rows_left, int wave, int lane) {
+  constexpr int W = 16 / kCopies;
+  DmaOffs<kCopies> t;
+#pragma unroll
+  for (int i = 0; i < kCopies; ++i) {
+    const int row = 4 * (wave + i * W) + (lane >> 4);
+    const int chunk = (lane & 15) ^ (row & 15);
+    t.o[i] = (uint32_t)(min(row, rows_left - 1) * (int)row_stride_elems * 2 + chunk * 16);
+  }
+  return t;
+}
+
+template <int kCopies>
+__device__ __forceinline__ void dma_tile_n(const char* tile_ptr /* uniform */, const DmaOffs<kCopies>& off, char* lds_tile,
+                                           int wave) {
+  constexpr int W = 16 / kCopies;
+#pragma unroll
+  for (int i = 0; i < kCopies; ++i) dma16(tile_ptr + off.o[i], lds_tile + (wave + i * W) * 1024);
+}
+
+// A pre-built 16 KiB LDS image (see transpose_tiles) copied verbatim.
+template <int kCopies>
+__device__ __forceinline__ void dma_tile_image(const char* image /* uniform */, char* lds_tile, int wave, int lane) {
+  constexpr int W = 16 / kCopies;
+#pragma unroll
+  for (int i = 0; i < kCopies; ++i) dma16(image + (wave + i * W) * 1024 + lane * 16, lds_tile + (wave + i * W) * 1024);
+}
+
 }  // namespace mmsp

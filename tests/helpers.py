@@ -68,8 +68,10 @@ class RankProblem:
         o_part = lse_part = None
         if not fused_merge:
             o_part, lse_part = torch.empty_like(o_acc), torch.empty_like(lse)
+        ws_bytes = ring.workspace_bytes(shape, n, n)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=DEV)
         ring.rank_forward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, o_acc, lse, o_final,
-                          fused_merge=fused_merge, o_part=o_part, lse_part=lse_part)
+                          fused_merge=fused_merge, o_part=o_part, lse_part=lse_part, ws=ws, ws_bytes=ws_bytes)
         out = dict(o_acc=o_acc, lse=lse, o_final=o_final)
         if do is not None:
             dod = to_dev(do, self.bf16)
@@ -77,7 +79,8 @@ class RankProblem:
             dq = torch.zeros_like(o_acc)
             dk = torch.zeros(self.N, n, self.Hkv, self.d, dtype=torch.float32, device=DEV)
             dv = torch.zeros_like(dk)
-            ring.rank_backward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, o_final, dod, lse, delta, dq, dk, dv)
+            ring.rank_backward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, o_final, dod, lse, delta, dq, dk, dv,
+                               ws=ws, ws_bytes=ws_bytes)
             out.update(delta=delta, dq=dq, dk_zz=dk, dv_zz=dv)
         torch.cuda.synchronize()
         return out

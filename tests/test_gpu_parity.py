@@ -96,7 +96,9 @@ def _run_step(io_bf16, Hq, Hkv, d, nq_tot, nk_tot, blk_kw, cu=None, seed=7, accu
     sentinel = 123.0
     o = torch.full((nq_tot, Hq, d), sentinel, dtype=torch.float32, device=DEV)
     lse = torch.full((Hq, nq_tot), sentinel, dtype=torch.float32, device=DEV)
-    B.mmsp_attn_step_fwd(shape, blk, qd, kd, vd, o, lse, 0)
+    ws_bytes = ring.workspace_bytes(shape, blk_kw["n_q"], blk_kw["n_k"])
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=DEV)
+    B.mmsp_attn_step_fwd(shape, blk, qd, kd, vd, o, lse, 0, ws, ws_bytes)
     torch.cuda.synchronize()
     ob = dict(q_row0=blk_kw["q_row0"], n_q=blk_kw["n_q"], k_row0=blk_kw["k_row0"], n_k=blk_kw["n_k"],
               q_pos0=blk_kw.get("q_pos0", 0), k_pos0=blk_kw.get("k_pos0", 0), mask=blk_kw["mask"])
@@ -119,7 +121,7 @@ def _run_step(io_bf16, Hq, Hkv, d, nq_tot, nk_tot, blk_kw, cu=None, seed=7, accu
     dq = torch.zeros((nq_tot, Hq, d), dtype=torch.float32, device=DEV)
     dk = torch.full((nk_tot, Hkv, d), sentinel, dtype=torch.float32, device=DEV)
     dv = torch.full((nk_tot, Hkv, d), sentinel, dtype=torch.float32, device=DEV)
-    B.mmsp_attn_step_bwd(shape, blk, qd, kd, vd, None, dod, lse_full, delta, 0, dq, dk, dv, 0)
+    B.mmsp_attn_step_bwd(shape, blk, qd, kd, vd, None, dod, lse_full, delta, 0, dq, dk, dv, 0, ws, ws_bytes)
     torch.cuda.synchronize()
     Dfull = np.zeros((Hq, nq_tot)); Dfull[:, r0:r1] = D_ref
     Lfull = np.zeros((Hq, nq_tot)); Lfull[:, r0:r1] = L_ref
@@ -132,7 +134,7 @@ def _run_step(io_bf16, Hq, Hkv, d, nq_tot, nk_tot, blk_kw, cu=None, seed=7, accu
     assert np.all(dkg[:k0] == sentinel) and np.all(dkg[k1:] == sentinel)
     assert np.all(dvg[:k0] == sentinel) and np.all(dvg[k1:] == sentinel)
     # accumulate_dkdv adds on top
-    B.mmsp_attn_step_bwd(shape, blk, qd, kd, vd, None, dod, lse_full, delta, 0, dq, dk, dv, 1)
+    B.mmsp_attn_step_bwd(shape, blk, qd, kd, vd, None, dod, lse_full, delta, 0, dq, dk, dv, 1, ws, ws_bytes)
     torch.cuda.synchronize()
     assert max_abs(to_host64(dk)[k0:k1], 2 * dk_ref) <= 2 * tol["g"]
     assert max_abs(to_host64(dq)[r0:r1], 2 * dq_ref) <= 2 * tol["g"]
@@ -240,7 +242,9 @@ def test_strided_q_and_kv_views():
         shape = ring.shape_for(qq, kk, B.MMSP_BF16, n)
         o = torch.empty((n, Hq, d), dtype=torch.float32, device=DEV)
         lse = torch.empty((Hq, n), dtype=torch.float32, device=DEV)
-        B.mmsp_attn_step_fwd(shape, blk, qq, kk, vv, o, lse, 0)
+        ws_bytes = ring.workspace_bytes(shape, n, n)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=DEV)
+        B.mmsp_attn_step_fwd(shape, blk, qq, kk, vv, o, lse, 0, ws, ws_bytes)
         torch.cuda.synchronize()
         outs.append((o, lse))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])

@@ -118,5 +118,15 @@ def test_null_and_misaligned_pointers_are_rejected():
     assert e.value.status == B.MMSP_ERR_INVALID_ARG                       # compute_delta without o_final
 
 
-def test_workspace_is_zero():
-    assert B.mmsp_workspace_bytes(_shape(), 8192, 8192, 1) == 0
+def test_workspace_size_and_rejection():
+    shape = _shape()
+    need = B.mmsp_workspace_bytes(shape, 200, 130, 0)
+    assert need >= 2 * 3 * 16384 and need % 16 == 0          # 2 KV heads x ceil(130/64) tiles of 16 KiB at least
+    assert B.mmsp_workspace_bytes(_shape(io_dtype=B.MMSP_F32, head_dim=64), 200, 130, 1) == 0
+    blk = B.make_block(0, 16, 0, 16, B.MMSP_MASK_FULL)
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_step_fwd(shape, blk, FAKE, FAKE, FAKE, FAKE, FAKE, 0, None, 0)
+    assert e.value.status == B.MMSP_ERR_WORKSPACE_TOO_SMALL
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_step_fwd(shape, blk, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 100)
+    assert e.value.status == B.MMSP_ERR_WORKSPACE_TOO_SMALL

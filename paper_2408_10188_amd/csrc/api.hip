@@ -91,9 +91,10 @@ mmsp_status device_result(hipError_t e, const char* what) {
 }
 
 // bf16 kernels read token-contiguous operands from pre-transposed tile images (16 KiB per 64
-// rows and head) that each call builds in the workspace: V^T for the forward.
+// rows and head) that each call builds in the workspace: V^T for the forward; Q^T, dO^T and the
+// padded row statistics for the backward.
 size_t needed_workspace(const mmsp_shape* s, int64_t n_q, int64_t n_k, bool backward) {
-  (void)n_q; (void)backward;
+  if (backward) return (size_t)mmsp::bwd_bf16_workspace_bytes(s->n_q_heads, n_q);
   return (size_t)(s->n_kv_heads * mmsp::tiles_of(n_k) * mmsp::kImageBytes);
 }
 
@@ -228,7 +229,6 @@ mmsp_status mmsp_attn_step_bwd(const mmsp_shape* shape, const mmsp_block* blk, c
                                const void* v, const void* o_final, const void* d_o, const float* lse_final,
                                float* delta, int compute_delta, float* dq_acc, float* dk, float* dv,
                                int accumulate_dkdv, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   mmsp_status st = check_shape(shape);
   if (st != MMSP_OK) return st;
   st = check_block(shape, blk);
@@ -256,7 +256,10 @@ mmsp_status mmsp_attn_step_bwd(const mmsp_shape* shape, const mmsp_block* blk, c
     if (e == hipSuccess) e = mmsp::launch_zero_f32(dv + first, count, stream);
     return device_result(e, "zero dk/dv");
   }
+  st = check_workspace(shape, blk, true, workspace, workspace_bytes);
+  if (st != MMSP_OK) return st;
   mmsp::StepArgs a = make_args(shape, blk);
+  a.ws = reinterpret_cast<char*>(workspace);
   a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.lse_final = lse_final; a.delta = delta;
   a.dq = dq_acc; a.dk = dk; a.dv = dv; a.accumulate = accumulate_dkdv != 0;
   if (shape->io_dtype == MMSP_BF16) return device_result(mmsp::launch_bwd_bf16(a, stream), "step_bwd (bf16)");

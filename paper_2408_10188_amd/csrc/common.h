@@ -31,6 +31,15 @@ struct StepArgs {
   char* ws;                     // caller's workspace (bf16 kernels)
 };
 
+// Workspace views of one backward call (all inside the caller's workspace).
+struct BwdWorkspace {
+  const char* qt;      // Q^T tile images   [Hq][n_qtiles][16 KiB]
+  const char* dot;     // dO^T tile images  [Hq][n_qtiles][16 KiB]
+  const float* nl2;    // -LSE*log2e, [Hq][n_qtiles*64], -inf where LSE = -inf and in the padding
+  const float* dl;     // delta,      [Hq][n_qtiles*64], 0 in the padding
+  int32_t n_qtiles;
+};
+
 constexpr int64_t kImageBytes = 16384;                       // one transposed 64x128 bf16 tile
 __host__ __device__ inline int64_t tiles_of(int64_t rows) { return (rows + 63) / 64; }
 
@@ -89,6 +98,13 @@ hipError_t launch_delta(const void* o_final, const void* d_o, float* delta, int 
 // the transposed LDS tile (TileT) in `out` at ((head * n_tiles + tile) * 16384).
 hipError_t launch_transpose_tiles(const void* x, int64_t tok_stride, int64_t head_stride, int H, int row0, int n_rows,
                                   void* out, hipStream_t stream);
+
+// Padded per-row statistics of the backward: nl2 = -LSE*log2e (or -inf), dl = delta.
+hipError_t launch_bwd_stats(const float* lse, const float* delta, int64_t lse_hs, int Hq, int row0, int n_rows,
+                            float* nl2, float* dl, hipStream_t stream);
+hipError_t launch_bwd_dkdv_bf16(const StepArgs& a, const BwdWorkspace& w, hipStream_t stream);
+int64_t bwd_bf16_workspace_bytes(int Hq, int64_t n_q);
+hipError_t bwd_bf16_prepare(const StepArgs& a, BwdWorkspace& w, hipStream_t stream);
 
 hipError_t launch_fwd_f32(const StepArgs& a, hipStream_t stream);
 hipError_t launch_bwd_f32(const StepArgs& a, hipStream_t stream);

@@ -153,6 +153,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
         s = mfma32(*reinterpret_cast<const u32x4*>(cur + na[ks] + qb * 8192), kreg[ks], s);
         dp = mfma32(*reinterpret_cast<const u32x4*>(cur + na[ks] + qb * 8192 + kTileBytes), vreg[ks], dp);
       }
+      __builtin_amdgcn_sched_barrier(0);    // keep each phase's operand reads inside the phase
       if (need_mask) {                    // only tiles that cut an interval boundary
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -179,6 +180,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
       const u32x4 pb1 = mk4(pack2(p[8], p[9]), pack2(p[10], p[11]), pack2(p[12], p[13]), pack2(p[14], p[15]));
       const u32x4 sb0 = mk4(pack2(ds[0], ds[1]), pack2(ds[2], ds[3]), pack2(ds[4], ds[5]), pack2(ds[6], ds[7]));
       const u32x4 sb1 = mk4(pack2(ds[8], ds[9]), pack2(ds[10], ds[11]), pack2(ds[12], ds[13]), pack2(ds[14], ds[15]));
+      __builtin_amdgcn_sched_barrier(0);
       // dV^T += dO^T P, dK^T += Q^T dS
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
@@ -187,13 +189,18 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
         dk[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + ta[(qb * 2) ^ db] + db * 4096), sb0, dk[db]);
         dk[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + ta[(qb * 2 + 1) ^ db] + db * 4096), sb1, dk[db]);
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  for (int it = 0; it < niter; it += 2) {               // two bodies so that LDS offsets are immediates
+  // Two bodies per trip so that LDS offsets are immediates; the odd last tile is peeled so
+  // that no accumulator crosses a conditional inside the loop.
+  int it = 0;
+  for (; it + 1 < niter; it += 2) {
     tile_body(it, stage0, stat0, stage1, stat1);
-    if (it + 1 < niter) tile_body(it + 1, stage1, stat1, stage0, stat0);
+    tile_body(it + 1, stage1, stat1, stage0, stat0);
   }
+  if (it < niter) tile_body(it, stage0, stat0, stage1, stat1);
 
   if (!live) return;
   const int64_t off = ((int64_t)(a.k_row0 + key) * a.Hkv + kvh) * 128 + half * 4;

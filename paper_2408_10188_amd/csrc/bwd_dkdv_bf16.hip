@@ -27,6 +27,9 @@ __device__ __forceinline__ void dma4(const char* gptr, char* lds_wave_base) {
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 4, 0, 0);
 }
 
+// kMask = false: the host has checked that every (query, key) pair of the block is visible and
+// that n_q is a multiple of the tile length, so no tile needs masking.
+template <bool kMask>
 __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWorkspace w, int n_kt, int xcd_per_kv) {
   __shared__ __attribute__((aligned(1024))) char stage0[kStage];   // Q TileN | dO TileN | Q^T TileT | dO^T TileT
   __shared__ __attribute__((aligned(1024))) char stage1[kStage];
@@ -131,6 +134,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
   auto advance = [&](int& hg, int& qt) { if (++qt > qt1) { qt = qt0; ++hg; } };
   if (niter > 0) advance(nxt_hg, nxt_qt);
 
+  // One 64-row tile.  The two 32-query blocks are software-pipelined inside the wavefront: the
+  // exp / dS arithmetic of one block is issued between the MFMAs of the other, so the vector
+  // ALU works while the matrix pipe is busy (there is only one wavefront per SIMD to overlap).
   auto tile_body = [&](int it, const char* cur, const float* stat, char* nxt, float* nstat) {
     // own copies of this tile have landed; after the barrier everybody's have, and everybody
     // is done reading the other stage, which is then refilled
@@ -140,57 +146,96 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
     advance(nxt_hg, nxt_qt);
     const int q0 = cur_qt * kBQ;
     if (++cur_qt > qt1) cur_qt = qt0;
-    const bool need_mask = q0 < w_lo_max || q0 + kBQ - 1 > w_hi_min;
+    // masked variant: rows outside [rlo, rhi] of this lane's key are hidden; tiles that lie
+    // wholly inside every key's interval get an interval that hides nothing
+    const bool need_mask = kMask && (q0 < w_lo_max || q0 + kBQ - 1 > w_hi_min);
+    const int m_base = need_mask ? q0 - rlo : 0;               // (row - rlo) as unsigned must be <= m_span
+    const unsigned m_span = need_mask ? (unsigned)(rhi - rlo) : 0x7fffffffu;   // rhi < rlo -> huge -> fix below
+    const bool m_none = need_mask && rhi < rlo;                // this key sees no row at all
 
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      // S = Q K^T, dP = dO V^T for 32 queries x this wavefront's 32 keys
-      f32x16 s, dp;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        s = mfma32(*reinterpret_cast<const u32x4*>(cur + na[ks] + qb * 8192), kreg[ks], s);
-        dp = mfma32(*reinterpret_cast<const u32x4*>(cur + na[ks] + qb * 8192 + kTileBytes), vreg[ks], dp);
+    f32x16 s0, dp0, s1, dp1;
+    uint32_t pw0[8], sw0[8], pw1[8], sw1[8];          // packed P / dS of the two blocks (B operands)
+
+    // operand of the j-th S/dP MFMA of block qb: even j -> Q tile (x K), odd j -> dO tile (x V)
+    auto sdp_operand = [&](int qb, int j) {
+      return *reinterpret_cast<const u32x4*>(cur + na[j >> 1] + qb * 8192 + (j & 1) * kTileBytes);
+    };
+    // operand of the j-th dV/dK MFMA of block qb: j = t*8 + db*2 + x, x = 0 -> dO^T (x P), 1 -> Q^T (x dS)
+    auto dvdk_operand = [&](int qb, int j) {
+      const int t = j >> 3, db = (j >> 1) & 3, x = j & 1;
+      return *reinterpret_cast<const u32x4*>(cur + ta[(qb * 2 + t) ^ db] + db * 4096 + (1 - x) * kTileBytes);
+    };
+    // element i of a block: P = exp2(S*c - LSE*log2e), dS = P * (dP - delta); packs pairs
+    float4 nl, dl;
+    float p_prev = 0.f, ds_prev = 0.f;
+    auto element = [&](int qb, int i, const f32x16& s, const f32x16& dp, uint32_t* pw, uint32_t* sw) {
+      const int qoff = qb * 32 + (i >> 2) * 8 + half * 4;     // tile-relative query of C register 4*(i/4)
+      if ((i & 3) == 0) {
+        nl = *reinterpret_cast<const float4*>(stat + qoff);
+        dl = *reinterpret_cast<const float4*>(stat + 64 + qoff);
       }
-      __builtin_amdgcn_sched_barrier(0);    // keep each phase's operand reads inside the phase
-      if (need_mask) {                    // only tiles that cut an interval boundary
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int qrow = q0 + qb * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
-          s[i] = (qrow < rlo || qrow > rhi) ? -INFINITY : s[i];
-        }
+      const float nle = (i & 3) == 0 ? nl.x : (i & 3) == 1 ? nl.y : (i & 3) == 2 ? nl.z : nl.w;
+      const float dle = (i & 3) == 0 ? dl.x : (i & 3) == 1 ? dl.y : (i & 3) == 2 ? dl.z : dl.w;
+      float sv = s[i];
+      if (kMask) {   // branch-free select
+        const bool hidden = (unsigned)(m_base + qoff + (i & 3)) > m_span || m_none;
+        sv = hidden ? -INFINITY : sv;
       }
-      // P = exp2(S*c - LSE*log2e), dS = P * (dP - delta), packed as B operands
-      float p[16], ds[16];
+      const float p = __builtin_amdgcn_exp2f(fmaf(sv, c, nle));
+      const float ds = p * (dp[i] - dle);
+      if (i & 1) { pw[i >> 1] = pack2(p_prev, p); sw[i >> 1] = pack2(ds_prev, ds); }
+      else { p_prev = p; ds_prev = ds; }
+    };
+
+    u32x4 op[16];
+    // ---- region A: S0, dP0 (matrix pipe only) ----
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int qoff = qb * 32 + g4 * 8 + half * 4;    // tile-relative query of C register 4*g4
-        const float4 nl = *reinterpret_cast<const float4*>(stat + qoff);
-        const float4 dl = *reinterpret_cast<const float4*>(stat + 64 + qoff);
-        const float nls[4] = {nl.x, nl.y, nl.z, nl.w}, dls[4] = {dl.x, dl.y, dl.z, dl.w};
+    for (int j = 0; j < 16; ++j) op[j] = sdp_operand(0, j);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = g4 * 4 + e;
-          p[i] = __builtin_amdgcn_exp2f(fmaf(s[i], c, nls[e]));
-          ds[i] = p[i] * (dp[i] - dls[e]);
-        }
-      }
-      const u32x4 pb0 = mk4(pack2(p[0], p[1]), pack2(p[2], p[3]), pack2(p[4], p[5]), pack2(p[6], p[7]));
-      const u32x4 pb1 = mk4(pack2(p[8], p[9]), pack2(p[10], p[11]), pack2(p[12], p[13]), pack2(p[14], p[15]));
-      const u32x4 sb0 = mk4(pack2(ds[0], ds[1]), pack2(ds[2], ds[3]), pack2(ds[4], ds[5]), pack2(ds[6], ds[7]));
-      const u32x4 sb1 = mk4(pack2(ds[8], ds[9]), pack2(ds[10], ds[11]), pack2(ds[12], ds[13]), pack2(ds[14], ds[15]));
-      __builtin_amdgcn_sched_barrier(0);
-      // dV^T += dO^T P, dK^T += Q^T dS
+    for (int i = 0; i < 16; ++i) { s0[i] = 0.f; dp0[i] = 0.f; s1[i] = 0.f; dp1[i] = 0.f; }
 #pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        dv[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + ta[(qb * 2) ^ db] + db * 4096 + kTileBytes), pb0, dv[db]);
-        dv[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + ta[(qb * 2 + 1) ^ db] + db * 4096 + kTileBytes), pb1, dv[db]);
-        dk[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + ta[(qb * 2) ^ db] + db * 4096), sb0, dk[db]);
-        dk[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + ta[(qb * 2 + 1) ^ db] + db * 4096), sb1, dk[db]);
-      }
+    for (int j = 0; j < 16; ++j) {
+      if (j & 1) dp0 = mfma32(op[j], vreg[j >> 1], dp0); else s0 = mfma32(op[j], kreg[j >> 1], s0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- region B: S1, dP1 on the matrix pipe, element j of block 0 on the vector ALU ----
+#pragma unroll
+    for (int j = 0; j < 8; ++j) op[j] = sdp_operand(1, j);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      if (j & 1) dp1 = mfma32(op[j], vreg[j >> 1], dp1); else s1 = mfma32(op[j], kreg[j >> 1], s1);
+      if (j < 8) op[8 + j] = sdp_operand(1, 8 + j);
+      element(0, j, s0, dp0, pw0, sw0);
       __builtin_amdgcn_sched_barrier(0);
     }
+    // ---- region C: dV, dK of block 0 on the matrix pipe, element j of block 1 on the vector ALU ----
+    {
+      const u32x4 pb[2] = {mk4(pw0[0], pw0[1], pw0[2], pw0[3]), mk4(pw0[4], pw0[5], pw0[6], pw0[7])};
+      const u32x4 sb[2] = {mk4(sw0[0], sw0[1], sw0[2], sw0[3]), mk4(sw0[4], sw0[5], sw0[6], sw0[7])};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) op[j] = dvdk_operand(0, j);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int t = j >> 3, db = (j >> 1) & 3;
+        if (j & 1) dk[db] = mfma32(op[j], sb[t], dk[db]); else dv[db] = mfma32(op[j], pb[t], dv[db]);
+        if (j < 8) op[8 + j] = dvdk_operand(0, 8 + j);
+        element(1, j, s1, dp1, pw1, sw1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // ---- region D: dV, dK of block 1 (matrix pipe only) ----
+    {
+      const u32x4 pb[2] = {mk4(pw1[0], pw1[1], pw1[2], pw1[3]), mk4(pw1[4], pw1[5], pw1[6], pw1[7])};
+      const u32x4 sb[2] = {mk4(sw1[0], sw1[1], sw1[2], sw1[3]), mk4(sw1[4], sw1[5], sw1[6], sw1[7])};
+#pragma unroll
+      for (int j = 0; j < 16; ++j) op[j] = dvdk_operand(1, j);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int t = j >> 3, db = (j >> 1) & 3;
+        if (j & 1) dk[db] = mfma32(op[j], sb[t], dk[db]); else dv[db] = mfma32(op[j], pb[t], dv[db]);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
   };
 
   // Two bodies per trip so that LDS offsets are immediates; the odd last tile is peeled so
@@ -232,7 +277,9 @@ hipError_t launch_bwd_dkdv_bf16(const StepArgs& a, const BwdWorkspace& w, hipStr
     xcd_per_kv = 8 / a.Hkv;
     n_blocks = 8 * ((n_kt + xcd_per_kv - 1) / xcd_per_kv);
   }
-  bwd_dkdv_bf16_kernel<<<dim3(n_blocks), dim3(256), 0, stream>>>(a, w, n_kt, xcd_per_kv);
+  const bool no_mask = a.mask == 0 && a.cu == nullptr && a.n_q % kBQ == 0;
+  if (no_mask) bwd_dkdv_bf16_kernel<false><<<dim3(n_blocks), dim3(256), 0, stream>>>(a, w, n_kt, xcd_per_kv);
+  else bwd_dkdv_bf16_kernel<true><<<dim3(n_blocks), dim3(256), 0, stream>>>(a, w, n_kt, xcd_per_kv);
   return hipGetLastError();
 }
 

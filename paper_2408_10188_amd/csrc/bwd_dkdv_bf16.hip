@@ -1,17 +1,19 @@
 // Backward ring step, dK/dV kernel (key-stationary) on bf16 matrix cores, head_dim 128.
 //
-// Workgroup = 4 wavefronts = 128 keys of one KV head; wavefront w owns 32 keys and keeps their
-// K and V rows (MFMA B operands, 64 VGPRs) and the dK^T / dV^T accumulators (2 x 128 d x 32
-// keys, 128 accumulator registers) for the whole call.  It streams 64-row tiles of Q and dO of
-// every query head of the group through a two-stage LDS ring filled by asynchronous
-// global->LDS copies: the natural tiles straight from the caller's tensors, the transposed
-// ones (Q^T, dO^T) from tile images that the call pre-builds in the workspace, and the per-row
-// statistics (-LSE*log2e, delta) from padded copies there.  Per 32-query block:
-//   S = Q K^T, dP = dO V^T           (A = Q / dO tile from LDS, B = K / V registers)
-//   P = exp2(S*c - LSE*log2e), dS = P * (dP - delta)     in S's register layout (lane = key)
-//   dV^T += dO^T P,  dK^T += Q^T dS  (A = transposed tile from LDS, B = P / dS from registers)
-// One wavefront per SIMD: the arithmetic of one block is written next to the matrix work of
-// the neighbouring block so the scheduler can overlap them.
+// Workgroup = 8 wavefronts = 128 keys of one KV head.  The wavefronts are specialised in pairs
+// that share 32 keys and, with the round-robin wavefront placement, a SIMD:
+//   "P" wavefront (0..3):  S = Q K^T,  P = exp2(S*c - LSE*log2e),  dV^T += dO^T P
+//   "D" wavefront (4..7):  dP = dO V^T,  dS = P * (dP - delta),    dK^T += Q^T dS
+// P travels from the first to the second through LDS, already packed as an MFMA B operand (the
+// two wavefronts use the same lane <-> (key, query) mapping, so it is a straight copy).  Each
+// wavefront keeps one 128 d x 32 key accumulator and one of K / V in registers, which fits the
+// plain VGPR file with two wavefronts per SIMD, and the two of a pair do the same number of
+// MFMAs, so one's exp / dS arithmetic overlaps the other's matrix work.
+//
+// 64-row tiles of Q and dO of every query head of the group stream through a two-stage LDS
+// ring filled by asynchronous global->LDS copies: the natural tiles straight from the caller's
+// tensors, the transposed ones (Q^T, dO^T) from tile images pre-built in the workspace, the
+// per-row statistics (-LSE*log2e, delta) from padded copies there.
 #include "mfma_tiles.h"
 
 namespace mmsp {
@@ -19,8 +21,9 @@ namespace {
 
 constexpr int kKeys = 128;          // keys per workgroup
 constexpr int kBQ = 64;             // query rows per streamed tile
-constexpr int kCopies = 4;          // 16 copies per tile / 4 wavefronts
-constexpr int kStage = 4 * kTileBytes;
+constexpr int kWaves = 8;
+constexpr int kCopies = 16 / kWaves;
+constexpr int kStage = 4 * kTileBytes;   // Q TileN | dO TileN | Q^T TileT | dO^T TileT
 
 __device__ __forceinline__ void dma4(const char* gptr, char* lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
@@ -30,14 +33,17 @@ __device__ __forceinline__ void dma4(const char* gptr, char* lds_wave_base) {
 // kMask = false: the host has checked that every (query, key) pair of the block is visible and
 // that n_q is a multiple of the tile length, so no tile needs masking.
 template <bool kMask>
-__global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWorkspace w, int n_kt, int xcd_per_kv) {
-  __shared__ __attribute__((aligned(1024))) char stage0[kStage];   // Q TileN | dO TileN | Q^T TileT | dO^T TileT
+__global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWorkspace w, int n_kt, int xcd_per_kv) {
+  __shared__ __attribute__((aligned(1024))) char stage0[kStage];
   __shared__ __attribute__((aligned(1024))) char stage1[kStage];
-  __shared__ __attribute__((aligned(1024))) float stat0[256];      // [0,64) -LSE*log2e, [64,128) delta, rest unused
-  __shared__ __attribute__((aligned(1024))) float stat1[256];
+  __shared__ __attribute__((aligned(1024))) float stat0[128];      // [0,64) -LSE*log2e, [64,128) delta
+  __shared__ __attribute__((aligned(1024))) float stat1[128];
+  __shared__ __attribute__((aligned(1024))) char pxch[2 * 4 * 2048];   // P of a block: [slot][pair][lane * 32 B]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, col = lane & 31;
+  const int pair = wave & 3;                    // which 32 keys
+  const bool role_p = wave < 4;                 // true: S / P / dV,  false: dP / dS / dK
 
   int kvh, kt;
   if (xcd_per_kv > 0) {             // workgroups of one KV head share an XCD (its L2 then serves the Q/dO stream once)
@@ -50,7 +56,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
     kt = blockIdx.x % n_kt;
   }
   const int tile_key0 = kt * kKeys;
-  const int key = tile_key0 + wave * 32 + col;           // block-relative key of this lane
+  const int key = tile_key0 + pair * 32 + col;           // block-relative key of this lane
   const bool live = key < a.n_k;
   const int keyc = min(key, a.n_k - 1);
 
@@ -62,7 +68,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
   row_interval_of_key(a, min(tile_key0 + kKeys, a.n_k) - 1, dummy, t_hi);
   int w_lo_max, w_hi_min;
   {
-    const int wk0 = min(tile_key0 + wave * 32, a.n_k - 1);
+    const int wk0 = min(tile_key0 + pair * 32, a.n_k - 1);
     row_interval_of_key(a, wk0, dummy, w_hi_min);
     w_lo_max = __shfl(rlo, 31);                          // last key of the wavefront (n_q for a dead key: always mask)
   }
@@ -75,7 +81,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
   const int ntiles = qt1 - qt0 + 1;
   const int niter = ntiles > 0 ? ntiles * a.group : 0;
 
-  // ---- asynchronous tile fetch ----
+  // ---- asynchronous tile fetch (all 8 wavefronts share the copies) ----
   const char* qbase = reinterpret_cast<const char*>(a.q) + (int64_t)a.q_row0 * a.q_ts * 2;
   const char* dobase = reinterpret_cast<const char*>(a.d_o) + (int64_t)a.q_row0 * a.Hq * 256;
   const int64_t q_tile_bytes = (int64_t)kBQ * a.q_ts * 2, do_tile_bytes = (int64_t)kBQ * a.Hq * 256;
@@ -96,47 +102,42 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
     const int64_t img = ((int64_t)h * w.n_qtiles + qt) * kImageBytes;
     dma_tile_image<kCopies>(w.qt + img, stage + 2 * kTileBytes, wave, lane);
     dma_tile_image<kCopies>(w.dot + img, stage + 3 * kTileBytes, wave, lane);
-    // statistics: wavefront 0 -> -LSE*log2e, 1 -> delta (2 and 3 repeat them into the unused half)
+    // statistics: even wavefronts fetch -LSE*log2e, odd ones delta (several fetch the same bytes)
     const float* src = ((wave & 1) ? w.dl : w.nl2) + (int64_t)h * w.n_qtiles * kBQ + qt * kBQ + lane;
-    dma4(reinterpret_cast<const char*>(src), reinterpret_cast<char*>(stat + wave * 64));
+    dma4(reinterpret_cast<const char*>(src), reinterpret_cast<char*>(stat + (wave & 1) * 64));
   };
   if (niter > 0) fetch(0, qt0, stage0, stat0);
 
-  // K, V rows of this lane's key as B operands (k index along d)
-  u32x4 kreg[8], vreg[8];
+  // K (P role) or V (D role) rows of this lane's key as B operands (k index along d)
+  u32x4 kvreg[8];
   {
     const int64_t off = (int64_t)(a.k_row0 + keyc) * a.kv_ts + (int64_t)kvh * a.kv_hs + half * 8;
-    const uint16_t* kp = reinterpret_cast<const uint16_t*>(a.k) + off;
-    const uint16_t* vp = reinterpret_cast<const uint16_t*>(a.v) + off;
+    const uint16_t* p = reinterpret_cast<const uint16_t*>(role_p ? a.k : a.v) + off;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      kreg[ks] = *reinterpret_cast<const u32x4*>(kp + ks * 16);
-      vreg[ks] = *reinterpret_cast<const u32x4*>(vp + ks * 16);
-    }
+    for (int ks = 0; ks < 8; ++ks) kvreg[ks] = *reinterpret_cast<const u32x4*>(p + ks * 16);
   }
   const float c = a.scale * kLog2e;
 
-  f32x16 dk[4], dv[4];
+  f32x16 acc[4];                                         // dV^T (P role) or dK^T (D role): 128 d x 32 keys
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { dk[db][i] = 0.f; dv[db][i] = 0.f; }
+    for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
 
-  // LDS read offsets, fixed for the whole call
+  // LDS read offsets, fixed for the whole call.  P role reads Q (natural) and dO^T; D role
+  // reads dO (natural) and Q^T.
   int na[8], ta[4];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) na[ks] = tile_n_offset(col, ks * 2 + half);         // + qb*8192 (+ kTileBytes for dO)
+  for (int ks = 0; ks < 8; ++ks) na[ks] = tile_n_offset(col, ks * 2 + half) + (role_p ? 0 : kTileBytes);            // + qb*8192
 #pragma unroll
-  for (int x = 0; x < 4; ++x) ta[x] = 2 * kTileBytes + tile_t_offset(col, x * 2 + half);   // + db*4096 (+ kTileBytes for dO^T)
+  for (int x = 0; x < 4; ++x) ta[x] = tile_t_offset(col, x * 2 + half) + (role_p ? 3 : 2) * kTileBytes;             // + db*4096
+  char* const my_px = pxch + pair * 2048 + lane * 32;    // + slot * 8192
 
   // (head of the group, query tile) of the tile being computed and of the one being fetched
   int cur_qt = qt0, nxt_hg = 0, nxt_qt = qt0;
   auto advance = [&](int& hg, int& qt) { if (++qt > qt1) { qt = qt0; ++hg; } };
   if (niter > 0) advance(nxt_hg, nxt_qt);
 
-  // One 64-row tile.  The two 32-query blocks are software-pipelined inside the wavefront: the
-  // exp / dS arithmetic of one block is issued between the MFMAs of the other, so the vector
-  // ALU works while the matrix pipe is busy (there is only one wavefront per SIMD to overlap).
   auto tile_body = [&](int it, const char* cur, const float* stat, char* nxt, float* nstat) {
     // own copies of this tile have landed; after the barrier everybody's have, and everybody
     // is done reading the other stage, which is then refilled
@@ -146,96 +147,65 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
     advance(nxt_hg, nxt_qt);
     const int q0 = cur_qt * kBQ;
     if (++cur_qt > qt1) cur_qt = qt0;
-    // masked variant: rows outside [rlo, rhi] of this lane's key are hidden; tiles that lie
-    // wholly inside every key's interval get an interval that hides nothing
     const bool need_mask = kMask && (q0 < w_lo_max || q0 + kBQ - 1 > w_hi_min);
-    const int m_base = need_mask ? q0 - rlo : 0;               // (row - rlo) as unsigned must be <= m_span
-    const unsigned m_span = need_mask ? (unsigned)(rhi - rlo) : 0x7fffffffu;   // rhi < rlo -> huge -> fix below
-    const bool m_none = need_mask && rhi < rlo;                // this key sees no row at all
 
-    f32x16 s0, dp0, s1, dp1;
-    uint32_t pw0[8], sw0[8], pw1[8], sw1[8];          // packed P / dS of the two blocks (B operands)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      // first product of the block: S = Q K^T (P role) or dP = dO V^T (D role)
+      f32x16 x;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) x[i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) x = mfma32(*reinterpret_cast<const u32x4*>(cur + na[ks] + qb * 8192), kvreg[ks], x);
 
-    // operand of the j-th S/dP MFMA of block qb: even j -> Q tile (x K), odd j -> dO tile (x V)
-    auto sdp_operand = [&](int qb, int j) {
-      return *reinterpret_cast<const u32x4*>(cur + na[j >> 1] + qb * 8192 + (j & 1) * kTileBytes);
-    };
-    // operand of the j-th dV/dK MFMA of block qb: j = t*8 + db*2 + x, x = 0 -> dO^T (x P), 1 -> Q^T (x dS)
-    auto dvdk_operand = [&](int qb, int j) {
-      const int t = j >> 3, db = (j >> 1) & 3, x = j & 1;
-      return *reinterpret_cast<const u32x4*>(cur + ta[(qb * 2 + t) ^ db] + db * 4096 + (1 - x) * kTileBytes);
-    };
-    // element i of a block: P = exp2(S*c - LSE*log2e), dS = P * (dP - delta); packs pairs
-    float4 nl, dl;
-    float p_prev = 0.f, ds_prev = 0.f;
-    auto element = [&](int qb, int i, const f32x16& s, const f32x16& dp, uint32_t* pw, uint32_t* sw) {
-      const int qoff = qb * 32 + (i >> 2) * 8 + half * 4;     // tile-relative query of C register 4*(i/4)
-      if ((i & 3) == 0) {
-        nl = *reinterpret_cast<const float4*>(stat + qoff);
-        dl = *reinterpret_cast<const float4*>(stat + 64 + qoff);
+      u32x4 b0, b1;                                      // B operands of the second product
+      char* px = my_px + qb * 8192;                      // exchange slot of this block
+      if (role_p) {
+        if (need_mask) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int qrow = q0 + qb * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
+            x[i] = (qrow < rlo || qrow > rhi) ? -INFINITY : x[i];
+          }
+        }
+        uint32_t pw[8];
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const float4 nl = *reinterpret_cast<const float4*>(stat + qb * 32 + g4 * 8 + half * 4);
+          pw[g4 * 2] = pack2(__builtin_amdgcn_exp2f(fmaf(x[g4 * 4 + 0], c, nl.x)),
+                             __builtin_amdgcn_exp2f(fmaf(x[g4 * 4 + 1], c, nl.y)));
+          pw[g4 * 2 + 1] = pack2(__builtin_amdgcn_exp2f(fmaf(x[g4 * 4 + 2], c, nl.z)),
+                                 __builtin_amdgcn_exp2f(fmaf(x[g4 * 4 + 3], c, nl.w)));
+        }
+        b0 = mk4(pw[0], pw[1], pw[2], pw[3]);
+        b1 = mk4(pw[4], pw[5], pw[6], pw[7]);
+        *reinterpret_cast<u32x4*>(px) = b0;
+        *reinterpret_cast<u32x4*>(px + 16) = b1;
       }
-      const float nle = (i & 3) == 0 ? nl.x : (i & 3) == 1 ? nl.y : (i & 3) == 2 ? nl.z : nl.w;
-      const float dle = (i & 3) == 0 ? dl.x : (i & 3) == 1 ? dl.y : (i & 3) == 2 ? dl.z : dl.w;
-      float sv = s[i];
-      if (kMask) {   // branch-free select
-        const bool hidden = (unsigned)(m_base + qoff + (i & 3)) > m_span || m_none;
-        sv = hidden ? -INFINITY : sv;
+      lds_barrier_after_write();                         // P of this block is in LDS
+      if (!role_p) {
+        const u32x4 p0 = *reinterpret_cast<const u32x4*>(px);
+        const u32x4 p1 = *reinterpret_cast<const u32x4*>(px + 16);
+        const uint32_t pw[8] = {p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
+        uint32_t sw[8];
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const float4 dl = *reinterpret_cast<const float4*>(stat + 64 + qb * 32 + g4 * 8 + half * 4);
+          const float pa = __uint_as_float(pw[g4 * 2] << 16), pb_ = __uint_as_float(pw[g4 * 2] & 0xffff0000u);
+          const float pc = __uint_as_float(pw[g4 * 2 + 1] << 16), pd = __uint_as_float(pw[g4 * 2 + 1] & 0xffff0000u);
+          sw[g4 * 2] = pack2(pa * (x[g4 * 4 + 0] - dl.x), pb_ * (x[g4 * 4 + 1] - dl.y));
+          sw[g4 * 2 + 1] = pack2(pc * (x[g4 * 4 + 2] - dl.z), pd * (x[g4 * 4 + 3] - dl.w));
+        }
+        b0 = mk4(sw[0], sw[1], sw[2], sw[3]);
+        b1 = mk4(sw[4], sw[5], sw[6], sw[7]);
       }
-      const float p = __builtin_amdgcn_exp2f(fmaf(sv, c, nle));
-      const float ds = p * (dp[i] - dle);
-      if (i & 1) { pw[i >> 1] = pack2(p_prev, p); sw[i >> 1] = pack2(ds_prev, ds); }
-      else { p_prev = p; ds_prev = ds; }
-    };
-
-    u32x4 op[16];
-    // ---- region A: S0, dP0 (matrix pipe only) ----
+      // second product: dV^T += dO^T P (P role) or dK^T += Q^T dS (D role)
 #pragma unroll
-    for (int j = 0; j < 16; ++j) op[j] = sdp_operand(0, j);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { s0[i] = 0.f; dp0[i] = 0.f; s1[i] = 0.f; dp1[i] = 0.f; }
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      if (j & 1) dp0 = mfma32(op[j], vreg[j >> 1], dp0); else s0 = mfma32(op[j], kreg[j >> 1], s0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // ---- region B: S1, dP1 on the matrix pipe, element j of block 0 on the vector ALU ----
-#pragma unroll
-    for (int j = 0; j < 8; ++j) op[j] = sdp_operand(1, j);
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      if (j & 1) dp1 = mfma32(op[j], vreg[j >> 1], dp1); else s1 = mfma32(op[j], kreg[j >> 1], s1);
-      if (j < 8) op[8 + j] = sdp_operand(1, 8 + j);
-      element(0, j, s0, dp0, pw0, sw0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // ---- region C: dV, dK of block 0 on the matrix pipe, element j of block 1 on the vector ALU ----
-    {
-      const u32x4 pb[2] = {mk4(pw0[0], pw0[1], pw0[2], pw0[3]), mk4(pw0[4], pw0[5], pw0[6], pw0[7])};
-      const u32x4 sb[2] = {mk4(sw0[0], sw0[1], sw0[2], sw0[3]), mk4(sw0[4], sw0[5], sw0[6], sw0[7])};
-#pragma unroll
-      for (int j = 0; j < 8; ++j) op[j] = dvdk_operand(0, j);
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int t = j >> 3, db = (j >> 1) & 3;
-        if (j & 1) dk[db] = mfma32(op[j], sb[t], dk[db]); else dv[db] = mfma32(op[j], pb[t], dv[db]);
-        if (j < 8) op[8 + j] = dvdk_operand(0, 8 + j);
-        element(1, j, s1, dp1, pw1, sw1);
-        __builtin_amdgcn_sched_barrier(0);
+      for (int db = 0; db < 4; ++db) {
+        acc[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + ta[(qb * 2) ^ db] + db * 4096), b0, acc[db]);
+        acc[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + ta[(qb * 2 + 1) ^ db] + db * 4096), b1, acc[db]);
       }
     }
-    // ---- region D: dV, dK of block 1 (matrix pipe only) ----
-    {
-      const u32x4 pb[2] = {mk4(pw1[0], pw1[1], pw1[2], pw1[3]), mk4(pw1[4], pw1[5], pw1[6], pw1[7])};
-      const u32x4 sb[2] = {mk4(sw1[0], sw1[1], sw1[2], sw1[3]), mk4(sw1[4], sw1[5], sw1[6], sw1[7])};
-#pragma unroll
-      for (int j = 0; j < 16; ++j) op[j] = dvdk_operand(1, j);
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int t = j >> 3, db = (j >> 1) & 3;
-        if (j & 1) dk[db] = mfma32(op[j], sb[t], dk[db]); else dv[db] = mfma32(op[j], pb[t], dv[db]);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
   };
 
   // Two bodies per trip so that LDS offsets are immediates; the odd last tile is peeled so
@@ -249,22 +219,20 @@ __global__ __launch_bounds__(256, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWo
 
   if (!live) return;
   const int64_t off = ((int64_t)(a.k_row0 + key) * a.Hkv + kvh) * 128 + half * 4;
+  float* out = (role_p ? a.dv : a.dk) + off;
+  const float mul = role_p ? 1.f : a.scale;
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int g4 = 0; g4 < 4; ++g4) {
-      float4* pk = reinterpret_cast<float4*>(a.dk + off + db * 32 + g4 * 8);
-      float4* pv = reinterpret_cast<float4*>(a.dv + off + db * 32 + g4 * 8);
-      float4 xk = make_float4(a.scale * dk[db][g4 * 4 + 0], a.scale * dk[db][g4 * 4 + 1],
-                              a.scale * dk[db][g4 * 4 + 2], a.scale * dk[db][g4 * 4 + 3]);
-      float4 xv = make_float4(dv[db][g4 * 4 + 0], dv[db][g4 * 4 + 1], dv[db][g4 * 4 + 2], dv[db][g4 * 4 + 3]);
+      float4* p = reinterpret_cast<float4*>(out + db * 32 + g4 * 8);
+      float4 x = make_float4(mul * acc[db][g4 * 4 + 0], mul * acc[db][g4 * 4 + 1], mul * acc[db][g4 * 4 + 2],
+                             mul * acc[db][g4 * 4 + 3]);
       if (a.accumulate) {
-        const float4 ok = *pk, ov = *pv;
-        xk.x += ok.x; xk.y += ok.y; xk.z += ok.z; xk.w += ok.w;
-        xv.x += ov.x; xv.y += ov.y; xv.z += ov.z; xv.w += ov.w;
+        const float4 o = *p;
+        x.x += o.x; x.y += o.y; x.z += o.z; x.w += o.w;
       }
-      *pk = xk;
-      *pv = xv;
+      *p = x;
     }
 }
 
@@ -278,8 +246,8 @@ hipError_t launch_bwd_dkdv_bf16(const StepArgs& a, const BwdWorkspace& w, hipStr
     n_blocks = 8 * ((n_kt + xcd_per_kv - 1) / xcd_per_kv);
   }
   const bool no_mask = a.mask == 0 && a.cu == nullptr && a.n_q % kBQ == 0;
-  if (no_mask) bwd_dkdv_bf16_kernel<false><<<dim3(n_blocks), dim3(256), 0, stream>>>(a, w, n_kt, xcd_per_kv);
-  else bwd_dkdv_bf16_kernel<true><<<dim3(n_blocks), dim3(256), 0, stream>>>(a, w, n_kt, xcd_per_kv);
+  if (no_mask) bwd_dkdv_bf16_kernel<false><<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, w, n_kt, xcd_per_kv);
+  else bwd_dkdv_bf16_kernel<true><<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, w, n_kt, xcd_per_kv);
   return hipGetLastError();
 }
 

@@ -171,6 +171,14 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("" ::: "memory");
 }
 
+// Same barrier for a wavefront that has just written LDS with ordinary ds_write instructions:
+// those are tracked by lgkmcnt, which must drain before the barrier so that the other
+// wavefronts see the data (vmcnt, i.e. the tile copies in flight, is left alone).
+__device__ __forceinline__ void lds_barrier_after_write() {
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+  lds_barrier();
+}
+
 // TileN by DMA: the tile is 16 wavefront-copies of 4 rows; copy j of a wavefront lands rows
 // 4j .. 4j+3.  Lane l of copy j fetches logical chunk (l % 16) ^ (row & 15) of row 4j + l/16.
 // kCopies = 16 / (wavefronts sharing the tile); the wavefront with index w takes copies

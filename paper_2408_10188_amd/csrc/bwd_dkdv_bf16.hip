@@ -149,6 +149,12 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
     if (++cur_qt > qt1) cur_qt = qt0;
     const bool need_mask = kMask && (q0 < w_lo_max || q0 + kBQ - 1 > w_hi_min);
 
+    // LDS operands are fetched a whole product ahead of the MFMAs that use them: those of the
+    // first product of block 0 here, those of a block's second product before its softmax /
+    // exchange, those of the next block's first product before the second product runs.
+    u32x4 o1[8], o2[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(cur + na[ks]);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       // first product of the block: S = Q K^T (P role) or dP = dO V^T (D role)
@@ -156,7 +162,13 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
 #pragma unroll
       for (int i = 0; i < 16; ++i) x[i] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) x = mfma32(*reinterpret_cast<const u32x4*>(cur + na[ks] + qb * 8192), kvreg[ks], x);
+      for (int ks = 0; ks < 8; ++ks) x = mfma32(o1[ks], kvreg[ks], x);
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        o2[2 * db] = *reinterpret_cast<const u32x4*>(cur + ta[(qb * 2) ^ db] + db * 4096);
+        o2[2 * db + 1] = *reinterpret_cast<const u32x4*>(cur + ta[(qb * 2 + 1) ^ db] + db * 4096);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 
       u32x4 b0, b1;                                      // B operands of the second product
       char* px = my_px + qb * 8192;                      // exchange slot of this block
@@ -200,10 +212,15 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
         b1 = mk4(sw[4], sw[5], sw[6], sw[7]);
       }
       // second product: dV^T += dO^T P (P role) or dK^T += Q^T dS (D role)
+      if (qb == 0) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(cur + na[ks] + 8192);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
-        acc[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + ta[(qb * 2) ^ db] + db * 4096), b0, acc[db]);
-        acc[db] = mfma32(*reinterpret_cast<const u32x4*>(cur + ta[(qb * 2 + 1) ^ db] + db * 4096), b1, acc[db]);
+        acc[db] = mfma32(o2[2 * db], b0, acc[db]);
+        acc[db] = mfma32(o2[2 * db + 1], b1, acc[db]);
       }
     }
   };

@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=32, help="query rows per chunk in the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy (scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the ring (one rank); this build has no multi-GPU path: "
@@ -50,6 +52,15 @@ def main():
     import torch
     from paper_2408_10188_amd import binding as B
     from paper_2408_10188_amd import ring, synth
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")       # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 3}))
+        return
 
     cfg = synth.CONFIGS[args.config]
     N, C, Hq, Hkv, d = cfg["N"], cfg["C"], cfg["Hq"], cfg["Hkv"], cfg["d"]

@@ -1,0 +1,136 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: outputs
+the oracle can compute one by one (sampled query rows: O, LSE, dQ; sampled key rows: dK, dV at
+the 65K configuration) and properties that hold at any size (column sums of the rank's dK/dV
+contribution).  The sampled values come from the same oracle code as the small tests; there is
+no independent pin at these sizes."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import mmsp_oracle as orc
+from paper_2408_10188_amd import binding as B
+from paper_2408_10188_amd import ring, synth
+from tests.helpers import DEV, RankProblem, max_abs, to_dev, to_host64
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(C, per_chunk, seed):
+    rng = np.random.default_rng(seed)
+    a = np.sort(rng.choice(C, per_chunk, replace=False))
+    b = np.sort(rng.choice(C, per_chunk, replace=False)) + C
+    rows = np.concatenate([a, b])
+    rows[0], rows[-1] = 0, 2 * C - 1            # first and last local row always included
+    return np.unique(rows)
+
+
+def _check_sampled_rows(prob, rank, out, q, do, rows, backward):
+    _, l2g = orc.zigzag_layout(prob.T, prob.N, rank)
+    K, V = prob.K_full().astype(np.float64), prob.V_full().astype(np.float64)
+    ref = orc.causal_attention(q[rows].astype(np.float64), K, V, prob.scale, q_pos=l2g[rows],
+                               dO=do[rows].astype(np.float64) if backward else None)
+    idx = torch.from_numpy(rows).to(DEV)
+    errs = dict(o=max_abs(to_host64(out["o_acc"][idx]), ref[0]), lse=max_abs(to_host64(out["lse"][:, idx]), ref[1]))
+    if backward:
+        errs["dq"] = max_abs(to_host64(out["dq"][idx]), ref[2])
+    print(f"rank {rank}: sampled-row errors {errs}", flush=True)
+    assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 and errs.get("dq", 0) <= 2e-2, errs
+
+
+def _check_column_sums(prob, out, do):
+    """sum_j dV[j] = sum over the group's heads and the rank's rows of dO (rows of P sum to 1);
+    sum_j dK[j] = 0 up to the rounding of O inside delta."""
+    g = prob.Hq // prob.Hkv
+    dv_sum = to_host64(out["dv_zz"].sum(dim=(0, 1)))                       # [Hkv, d]
+    dk_sum = to_host64(out["dk_zz"].sum(dim=(0, 1)))
+    ref = do.astype(np.float64).sum(axis=0).reshape(prob.Hkv, g, prob.d).sum(axis=1)
+    n = do.shape[0] * g
+    assert max_abs(dv_sum, ref) <= 2e-3 * math.sqrt(n), max_abs(dv_sum, ref)   # bf16 rounding of P, random sign
+    assert np.abs(dk_sum).max() <= 2e-3 * math.sqrt(n) * 4, np.abs(dk_sum).max()
+
+
+def test_config2_forward_all_ranks_sampled_rows():
+    prob = RankProblem(synth.CONFIGS["cfg2"])
+    for r in range(prob.N):
+        q, do = prob.rank_inputs(r)
+        out = prob.run_gpu(r, q, None)
+        _check_sampled_rows(prob, r, out, q, do, _sample_rows(prob.C, 12, 100 + r), backward=False)
+
+
+@pytest.mark.parametrize("rank", [0, 7])
+def test_config3_fwd_bwd_sampled_rows_and_keys(rank):
+    prob = RankProblem(synth.CONFIGS["cfg3"])
+    q, do = prob.rank_inputs(rank)
+    out = prob.run_gpu(rank, q, do)
+    _check_sampled_rows(prob, rank, out, q, do, _sample_rows(prob.C, 6, 200 + rank), backward=True)
+    _check_column_sums(prob, out, do)
+    if rank != 0:
+        return
+    # dK/dV of sampled key rows of KV head 1: needs the oracle forward of every row of the rank for
+    # the 7 heads of that group (LSE, delta), then P and dS against the sampled keys only
+    kvh, g = 1, prob.Hq // prob.Hkv
+    heads = slice(kvh * g, (kvh + 1) * g)
+    _, l2g = orc.zigzag_layout(prob.T, prob.N, rank)
+    K = prob.K_full()[:, kvh:kvh + 1].astype(np.float64)
+    V = prob.V_full()[:, kvh:kvh + 1].astype(np.float64)
+    qh, doh = q[:, heads].astype(np.float64), do[:, heads].astype(np.float64)
+    O, LSE = orc.causal_attention(qh, K, V, prob.scale, q_pos=l2g, row_block=512)
+    D = orc.delta(doh, O)
+    keys = np.unique(np.concatenate([np.random.default_rng(7).choice(prob.T, 24, replace=False), [0, prob.C - 1, prob.T - 1]]))
+    vis = orc.visible(l2g, keys)
+    _, dk_ref, dv_ref = orc.attention_bwd(qh, K[keys], V[keys], doh, vis, prob.scale, LSE=LSE, D=D)
+    dk = prob.unzigzag(to_host64(out["dk_zz"]))[keys, kvh:kvh + 1]
+    dv = prob.unzigzag(to_host64(out["dv_zz"]))[keys, kvh:kvh + 1]
+    errs = (max_abs(dk, dk_ref), max_abs(dv, dv_ref))
+    print("sampled-key errors (dK, dV):", errs, flush=True)
+    assert max(errs) <= 2e-2, errs
+
+
+def test_long_shard_fwd_bwd_sampled_rows():
+    prob = RankProblem(synth.CONFIGS["long"])
+    q, do = prob.rank_inputs(0)
+    out = prob.run_gpu(0, q, do)
+    _check_sampled_rows(prob, 0, out, q, do, _sample_rows(prob.C, 4, 300), backward=True)
+    _check_column_sums(prob, out, do)
+
+
+def test_ulysses_packed_fwd_bwd_sampled_rows():
+    cfg = synth.CONFIGS["ulysses"]
+    T, Hq, Hkv, d = 2 * cfg["C"], cfg["Hq"], cfg["Hkv"], cfg["d"]
+    scale = 1 / math.sqrt(d)
+    Cg = 8192
+    gen = lambda name, H, sig: np.concatenate([synth.chunk(name, c, Cg, H, d, sig, cfg["seed"]) for c in range(T // Cg)])
+    q, k, v, do = gen("q", Hq, 0.5), gen("k", Hkv, 0.5), gen("v", Hkv, 0.5), gen("do", Hq, 1.0)
+    cu = synth.packed_cu_seqlens(T, cfg["seed"])
+    qd, kd, vd, dod = (to_dev(x, True) for x in (q, k, v, do))
+    cud = torch.from_numpy(cu).to(DEV)
+    shape = ring.shape_for(qd, kd, B.MMSP_BF16, T, scale)
+    o_acc = torch.empty(T, Hq, d, dtype=torch.float32, device=DEV)
+    lse = torch.empty(Hq, T, dtype=torch.float32, device=DEV)
+    o_final = torch.empty_like(qd)
+    delta = torch.empty_like(lse)
+    dq = torch.zeros_like(o_acc)
+    dk = torch.zeros(T, Hkv, d, dtype=torch.float32, device=DEV)
+    dv = torch.zeros_like(dk)
+    ws_bytes = ring.workspace_bytes(shape, T, T)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    ring.ulysses_forward(shape, T, qd, kd, vd, cud, len(cu) - 1, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes)
+    ring.ulysses_backward(shape, T, qd, kd, vd, cud, len(cu) - 1, o_final, dod, lse, delta, dq, dk, dv, ws=ws,
+                          ws_bytes=ws_bytes)
+    torch.cuda.synchronize()
+    # sampled rows: document starts, document ends, and random rows
+    rows = np.unique(np.concatenate([cu[:-1], cu[1:] - 1, np.random.default_rng(5).choice(T, 10, replace=False)]))
+    ref = orc.causal_attention(q[rows].astype(np.float64), k.astype(np.float64), v.astype(np.float64), scale,
+                               cu_seqlens=cu, q_pos=rows, dO=do[rows].astype(np.float64), row_block=4)
+    idx = torch.from_numpy(rows).to(DEV)
+    errs = dict(o=max_abs(to_host64(o_acc[idx]), ref[0]), lse=max_abs(to_host64(lse[:, idx]), ref[1]),
+                dq=max_abs(to_host64(dq[idx]), ref[2]))
+    print("ulysses sampled-row errors", errs, flush=True)
+    assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 and errs["dq"] <= 2e-2, errs
+    # per document: sum_j dV[j] = sum over heads and rows of the document of dO
+    dvh = to_host64(dv)
+    for a, b in zip(cu[:-1], cu[1:]):
+        ref_sum = do[a:b].astype(np.float64).sum(axis=(0, 1))
+        assert max_abs(dvh[a:b, 0].sum(axis=0), ref_sum) <= 2e-3 * math.sqrt((b - a) * Hq) + 1e-3

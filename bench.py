@@ -39,6 +39,7 @@ def main():
     ap.add_argument("--config", default="long", choices=["cfg3", "long"])
     ap.add_argument("--rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--one-stream", action="store_true", help="all launches on one stream (no overlap of ring steps)")
     ap.add_argument("--cpu-rows", type=int, default=32, help="query rows per chunk in the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -96,11 +97,18 @@ def main():
     ws_bytes = ring.workspace_bytes(shape, n, n)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 
+    # second launch lane (HIP stream, (O, LSE) accumulator, workspace): consecutive ring steps
+    # overlap so that the partly filled last round of one launch does not leave CUs idle
+    side = None
+    if not args.one_stream:
+        side = ring.SideLane(torch.cuda.Stream(), torch.empty_like(o_acc), torch.empty_like(lse),
+                             torch.empty_like(ws), ws_bytes)
+
     def one_pass():
-        ring.rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes)
+        ring.rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes, side=side)
         dq.zero_()
         ring.rank_backward(shape, T, N, rank, q, k_zz, v_zz, o_final, d_o, lse, delta, dq, dk_zz, dv_zz, ws=ws,
-                           ws_bytes=ws_bytes)
+                           ws_bytes=ws_bytes, side=side)
 
     for _ in range(args.warmup):
         one_pass()
@@ -125,6 +133,7 @@ def main():
 
     plans = [B.mmsp_zigzag_plan(T, N, rank, s) for s in range(N)]
     kinds = {"fwd_step": [], "merge_cast": [], "delta": [], "bwd_dq": [], "bwd_dkdv": []}
+    torch.cuda.synchronize()
     for _ in range(2):
         for s, (src, blk) in enumerate(plans):
             kinds["fwd_step"].append((timed(lambda: B.mmsp_attn_step_fwd(shape, blk, q, k_zz[src], v_zz[src], o_acc, lse, s > 0, ws, ws_bytes)), blk))
@@ -205,6 +214,7 @@ def main():
         "frac_of_bf16_dense_peak": value / BF16_DENSE_PEAK_TFLOPS,
         "config": {"workload": "%s: zigzag rank %d of N=%d, C=%d (T=%d), %d/%d heads, d=%d, bf16, fwd+bwd over all %d "
                                "ring steps" % (args.config, rank, N, C, T, Hq, Hkv, d, N),
+                   "streams": 1 if side is None else 2,
                    "pairs_per_head": pairs, "tflop_fwd": flops_fwd / 1e12, "tflop_bwd": flops_bwd / 1e12},
         "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown,
     }

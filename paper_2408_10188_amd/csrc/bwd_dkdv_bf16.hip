@@ -133,28 +133,34 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   for (int x = 0; x < 4; ++x) ta[x] = tile_t_offset(col, x * 2 + half) + (role_p ? 3 : 2) * kTileBytes;             // + db*4096
   char* const my_px = pxch + pair * 2048 + lane * 32;    // + slot * 8192
 
-  // (head of the group, query tile) of the tile being computed and of the one being fetched
-  int cur_qt = qt0, nxt_hg = 0, nxt_qt = qt0;
+  // (head of the group, query tile) of the tile being computed and of the next one to fetch,
+  // which runs two tiles ahead: both stages are filled before the loop starts.
+  int cur_qt = qt0, f_hg = 0, f_qt = qt0;
   auto advance = [&](int& hg, int& qt) { if (++qt > qt1) { qt = qt0; ++hg; } };
-  if (niter > 0) advance(nxt_hg, nxt_qt);
+  if (niter > 0) advance(f_hg, f_qt);
+  if (niter > 1) { fetch(f_hg, f_qt, stage1, stat1); advance(f_hg, f_qt); }
 
-  auto tile_body = [&](int it, const char* cur, const float* stat, char* nxt, float* nstat) {
-    // own copies of this tile have landed; after the barrier everybody's have, and everybody
-    // is done reading the other stage, which is then refilled
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): only this tile's copies are in flight here
-    lds_barrier();
-    if (it + 1 < niter) fetch(nxt_hg, nxt_qt, nxt, nstat);
-    advance(nxt_hg, nxt_qt);
+  // LDS operands are fetched a whole product ahead of the MFMAs that use them.  o1 feeds a
+  // block's first product (S or dP); it is reloaded for the next block as soon as the MFMAs
+  // that read it are issued, for the next tile's first block right after the barrier that hands
+  // the stages over.  o2 feeds the second product (dV or dK) and is loaded before the exchange.
+  u32x4 o1[8], o2[8];
+  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): K / V registers and both stages
+  lds_barrier();
+  if (niter > 0) {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(stage0 + na[ks]);
+  }
+
+  // One tile = two 32-row blocks and two workgroup barriers, one per block: before it the P
+  // wavefronts have published P of the block and everybody has finished every LDS read issued
+  // so far.  The second barrier of a tile therefore also retires the tile's stage, which is
+  // refilled at once with the tile after next, and publishes the next tile's stage (each
+  // wavefront waits for its own copies of it first).
+  auto tile_body = [&](int it, char* cur, float* stat, const char* oth) {
     const int q0 = cur_qt * kBQ;
     if (++cur_qt > qt1) cur_qt = qt0;
     const bool need_mask = kMask && (q0 < w_lo_max || q0 + kBQ - 1 > w_hi_min);
-
-    // LDS operands are fetched a whole product ahead of the MFMAs that use them: those of the
-    // first product of block 0 here, those of a block's second product before its softmax /
-    // exchange, those of the next block's first product before the second product runs.
-    u32x4 o1[8], o2[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(cur + na[ks]);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       // first product of the block: S = Q K^T (P role) or dP = dO V^T (D role)
@@ -167,6 +173,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
       for (int db = 0; db < 4; ++db) {
         o2[2 * db] = *reinterpret_cast<const u32x4*>(cur + ta[(qb * 2) ^ db] + db * 4096);
         o2[2 * db + 1] = *reinterpret_cast<const u32x4*>(cur + ta[(qb * 2 + 1) ^ db] + db * 4096);
+      }
+      if (qb == 0) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(cur + na[ks] + 8192);
       }
       __builtin_amdgcn_sched_barrier(0);
 
@@ -193,8 +203,26 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
         b1 = mk4(pw[4], pw[5], pw[6], pw[7]);
         *reinterpret_cast<u32x4*>(px) = b0;
         *reinterpret_cast<u32x4*>(px + 16) = b1;
+      } else {
+        // dP - delta before the barrier: the statistics belong to the stage being retired
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const float4 dl = *reinterpret_cast<const float4*>(stat + 64 + qb * 32 + g4 * 8 + half * 4);
+          x[g4 * 4 + 0] -= dl.x; x[g4 * 4 + 1] -= dl.y; x[g4 * 4 + 2] -= dl.z; x[g4 * 4 + 3] -= dl.w;
+        }
       }
-      lds_barrier_after_write();                         // P of this block is in LDS
+      if (qb == 0) {
+        lds_barrier_after_write();
+      } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): own copies of the next tile
+        lds_barrier_after_write();
+        if (it + 2 < niter) fetch(f_hg, f_qt, cur, stat);
+        advance(f_hg, f_qt);
+        if (it + 1 < niter) {
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(oth + na[ks]);
+        }
+      }
       if (!role_p) {
         const u32x4 p0 = *reinterpret_cast<const u32x4*>(px);
         const u32x4 p1 = *reinterpret_cast<const u32x4*>(px + 16);
@@ -202,21 +230,16 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
         uint32_t sw[8];
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-          const float4 dl = *reinterpret_cast<const float4*>(stat + 64 + qb * 32 + g4 * 8 + half * 4);
           const float pa = __uint_as_float(pw[g4 * 2] << 16), pb_ = __uint_as_float(pw[g4 * 2] & 0xffff0000u);
           const float pc = __uint_as_float(pw[g4 * 2 + 1] << 16), pd = __uint_as_float(pw[g4 * 2 + 1] & 0xffff0000u);
-          sw[g4 * 2] = pack2(pa * (x[g4 * 4 + 0] - dl.x), pb_ * (x[g4 * 4 + 1] - dl.y));
-          sw[g4 * 2 + 1] = pack2(pc * (x[g4 * 4 + 2] - dl.z), pd * (x[g4 * 4 + 3] - dl.w));
+          sw[g4 * 2] = pack2(pa * x[g4 * 4 + 0], pb_ * x[g4 * 4 + 1]);
+          sw[g4 * 2 + 1] = pack2(pc * x[g4 * 4 + 2], pd * x[g4 * 4 + 3]);
         }
         b0 = mk4(sw[0], sw[1], sw[2], sw[3]);
         b1 = mk4(sw[4], sw[5], sw[6], sw[7]);
       }
-      // second product: dV^T += dO^T P (P role) or dK^T += Q^T dS (D role)
-      if (qb == 0) {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(cur + na[ks] + 8192);
-      }
       __builtin_amdgcn_sched_barrier(0);
+      // second product: dV^T += dO^T P (P role) or dK^T += Q^T dS (D role)
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
         acc[db] = mfma32(o2[2 * db], b0, acc[db]);
@@ -229,10 +252,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   // that no accumulator crosses a conditional inside the loop.
   int it = 0;
   for (; it + 1 < niter; it += 2) {
-    tile_body(it, stage0, stat0, stage1, stat1);
-    tile_body(it + 1, stage1, stat1, stage0, stat0);
+    tile_body(it, stage0, stat0, stage1);
+    tile_body(it + 1, stage1, stat1, stage0);
   }
-  if (it < niter) tile_body(it, stage0, stat0, stage1, stat1);
+  if (it < niter) tile_body(it, stage0, stat0, stage1);
 
   if (!live) return;
   const int64_t off = ((int64_t)(a.k_row0 + key) * a.Hkv + kvh) * 128 + half * 4;

@@ -1,6 +1,13 @@
 """Host loop that drives one virtual rank through its N ring steps (zigzag mode) or through
-the single step of the Ulysses head-shard mode.  It only sequences C-ABI calls on one HIP
-stream; all arithmetic happens in the kernels.
+the single step of the Ulysses head-shard mode.  It only sequences C-ABI calls on HIP
+streams; all arithmetic happens in the kernels.
+
+A step's grid rarely fills the 256 CUs a whole number of times, so the last round of its
+workgroups leaves CUs idle.  With a `SideLane` the loop keeps two independent chains of
+launches in flight on two streams, whose tails fill each other: forward steps alternate between
+two (O, LSE) accumulators that one final merge combines (the merge is associative, so any
+split of the ring steps gives the same result up to rounding); in the backward the dQ kernels
+(chained through dq) run on one stream and the dK/dV kernels (independent per step) on the other.
 
 Device buffers (torch tensors, allocated by the caller):
   q, d_o, o_final   [2C, Hq, d]      io dtype, the rank's local rows (chunk r then chunk 2N-1-r)
@@ -28,11 +35,48 @@ def workspace_bytes(shape, n_q, n_k):
     return max(B.mmsp_workspace_bytes(shape, n_q, n_k, False), B.mmsp_workspace_bytes(shape, n_q, n_k, True))
 
 
+class SideLane:
+    """A second HIP stream (torch.cuda.Stream) with the buffers its launches need: an (O, LSE)
+    accumulator pair like (o_acc, lse) and a workspace of its own."""
+
+    def __init__(self, stream, o_acc, lse, ws, ws_bytes):
+        self.stream, self.o_acc, self.lse, self.ws, self.ws_bytes = stream, o_acc, lse, ws, ws_bytes
+
+    @property
+    def handle(self):
+        return self.stream.cuda_stream
+
+
+def _fork(side):
+    import torch
+    main = torch.cuda.current_stream()
+    side.stream.wait_stream(main)
+    return main
+
+
 def rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final=None, stream=0, fused_merge=True,
-                 o_part=None, lse_part=None, ws=None, ws_bytes=0):
+                 o_part=None, lse_part=None, ws=None, ws_bytes=0, side=None):
     """All N forward steps of `rank`.  fused_merge=True merges in the step kernel's epilogue;
-    otherwise every step writes (o_part, lse_part) and mmsp_attn_merge combines them."""
+    otherwise every step writes (o_part, lse_part) and mmsp_attn_merge combines them.
+    With `side` (fused merge only, launches on the current torch stream and on side.stream)
+    odd steps accumulate into the side lane and the final merge folds it in."""
     n_rows = q.shape[0]
+    if side is not None and N > 1:
+        main = _fork(side)
+        # rows that no odd step reaches must still hold an empty partial result
+        B.mmsp_attn_step_fwd(shape, B.make_block(0, n_rows, 0, 0, B.MMSP_MASK_NONE, 0, 0), q, k_zz[0], v_zz[0],
+                             side.o_acc, side.lse, False, side.ws, side.ws_bytes, side.handle)
+        for s in range(N):
+            src, blk = B.mmsp_zigzag_plan(T, N, rank, s)
+            if s & 1:
+                B.mmsp_attn_step_fwd(shape, blk, q, k_zz[src], v_zz[src], side.o_acc, side.lse, True, side.ws,
+                                     side.ws_bytes, side.handle)
+            else:
+                B.mmsp_attn_step_fwd(shape, blk, q, k_zz[src], v_zz[src], o_acc, lse, s > 0, ws, ws_bytes,
+                                     main.cuda_stream)
+        main.wait_stream(side.stream)
+        B.mmsp_attn_merge(shape, 0, n_rows, o_acc, lse, side.o_acc, side.lse, o_final, stream=main.cuda_stream)
+        return
     for s in range(N):
         src, blk = B.mmsp_zigzag_plan(T, N, rank, s)
         if fused_merge or s == 0:
@@ -45,9 +89,24 @@ def rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final=None, str
 
 
 def rank_backward(shape, T, N, rank, q, k_zz, v_zz, o_final, d_o, lse, delta, dq, dk_zz, dv_zz, stream=0, ws=None,
-                  ws_bytes=0):
-    """delta pre-pass, then all N backward steps of `rank`.  dq must be zero on entry."""
+                  ws_bytes=0, side=None):
+    """delta pre-pass, then all N backward steps of `rank`.  dq must be zero on entry.
+    With `side` the dQ kernels run on the current torch stream and the dK/dV kernels on
+    side.stream (with side's workspace)."""
     n_rows = q.shape[0]
+    if side is not None:
+        import torch
+        main = torch.cuda.current_stream()
+        B.mmsp_attn_delta(shape, 0, n_rows, o_final, d_o, delta, stream=main.cuda_stream)
+        side.stream.wait_stream(main)
+        for s in range(N):
+            src, blk = B.mmsp_zigzag_plan(T, N, rank, s)
+            B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, False, dq, None, None,
+                                 False, ws, ws_bytes, main.cuda_stream)
+            B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, False, None,
+                                 dk_zz[src], dv_zz[src], False, side.ws, side.ws_bytes, side.handle)
+        main.wait_stream(side.stream)
+        return
     B.mmsp_attn_delta(shape, 0, n_rows, o_final, d_o, delta, stream=stream)
     for s in range(N):
         src, blk = B.mmsp_zigzag_plan(T, N, rank, s)

@@ -56,8 +56,9 @@ class RankProblem:
         do = np.concatenate([self._g("do", c0, self.Hq, 1.0), self._g("do", c1, self.Hq, 1.0)])
         return q, do
 
-    def run_gpu(self, rank, q, do=None, fused_merge=True):
-        """Forward (and backward when do is given) of one rank through the C-ABI."""
+    def run_gpu(self, rank, q, do=None, fused_merge=True, two_streams=False):
+        """Forward (and backward when do is given) of one rank through the C-ABI; with two_streams
+        the ring steps alternate between two launch lanes (ring.SideLane)."""
         n = 2 * self.C
         qd = to_dev(q, self.bf16)
         io = B.MMSP_BF16 if self.bf16 else B.MMSP_F32
@@ -70,8 +71,12 @@ class RankProblem:
             o_part, lse_part = torch.empty_like(o_acc), torch.empty_like(lse)
         ws_bytes = ring.workspace_bytes(shape, n, n)
         ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=DEV)
+        side = None
+        if two_streams:
+            side = ring.SideLane(torch.cuda.Stream(), torch.empty_like(o_acc), torch.empty_like(lse),
+                                 torch.empty_like(ws), ws_bytes)
         ring.rank_forward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, o_acc, lse, o_final,
-                          fused_merge=fused_merge, o_part=o_part, lse_part=lse_part, ws=ws, ws_bytes=ws_bytes)
+                          fused_merge=fused_merge, o_part=o_part, lse_part=lse_part, ws=ws, ws_bytes=ws_bytes, side=side)
         out = dict(o_acc=o_acc, lse=lse, o_final=o_final)
         if do is not None:
             dod = to_dev(do, self.bf16)
@@ -80,7 +85,7 @@ class RankProblem:
             dk = torch.zeros(self.N, n, self.Hkv, self.d, dtype=torch.float32, device=DEV)
             dv = torch.zeros_like(dk)
             ring.rank_backward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, o_final, dod, lse, delta, dq, dk, dv,
-                               ws=ws, ws_bytes=ws_bytes)
+                               ws=ws, ws_bytes=ws_bytes, side=side)
             out.update(delta=delta, dq=dq, dk_zz=dk, dv_zz=dv)
         torch.cuda.synchronize()
         return out

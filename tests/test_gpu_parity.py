@@ -19,9 +19,9 @@ TOL_BF16 = dict(o=2e-2, lse=1e-3, g=2e-2)
 TOL_F32 = dict(o=1e-5, lse=1e-5, g=1e-5)
 
 
-def _check_rank(prob, rank, tol, fused_merge=True, backward=True):
+def _check_rank(prob, rank, tol, fused_merge=True, backward=True, two_streams=False):
     q, do = prob.rank_inputs(rank)
-    out = prob.run_gpu(rank, q, do if backward else None, fused_merge=fused_merge)
+    out = prob.run_gpu(rank, q, do if backward else None, fused_merge=fused_merge, two_streams=two_streams)
     _, l2g = orc.zigzag_layout(prob.T, prob.N, rank)
     K, V = prob.K_full().astype(np.float64), prob.V_full().astype(np.float64)
     ref = orc.causal_attention(q.astype(np.float64), K, V, prob.scale, q_pos=l2g,
@@ -59,6 +59,16 @@ def test_bf16_ring_small_ragged(Hq, Hkv, N, C):
     prob = RankProblem(cfg)
     for r in range(N):
         _check_rank(prob, r, TOL_BF16, fused_merge=(r % 2 == 0))
+
+
+@pytest.mark.parametrize("dtype,N,C,d", [("bf16", 4, 160, 128), ("bf16", 1, 128, 128), ("f32", 3, 64, 64)])
+def test_ring_on_two_launch_lanes(dtype, N, C, d):
+    """Ring steps alternating between two streams and two (O, LSE) accumulators, dQ and dK/dV
+    kernels on different streams: same results as the oracle, rows no odd step reaches included."""
+    cfg = dict(dtype=dtype, Hq=4, Hkv=2, d=d, N=N, C=C, sigma=0.5, seed=11)
+    prob = RankProblem(cfg)
+    for r in range(N):
+        _check_rank(prob, r, TOL_BF16 if dtype == "bf16" else TOL_F32, two_streams=True)
 
 
 def test_bf16_ring_reassembles_unsharded_result():

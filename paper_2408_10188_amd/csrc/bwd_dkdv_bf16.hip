@@ -87,26 +87,34 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   const int64_t q_tile_bytes = (int64_t)kBQ * a.q_ts * 2, do_tile_bytes = (int64_t)kBQ * a.Hq * 256;
   const DmaOffs<kCopies> qoff_full = dma_n_offsets<kCopies>(a.q_ts, kBQ, wave, lane);
   const DmaOffs<kCopies> dooff_full = dma_n_offsets<kCopies>((int64_t)a.Hq * 128, kBQ, wave, lane);
-  auto fetch = [&](int hg, int qt, char* stage, float* stat) {
+  // The copies of one tile are issued in four pieces (Q with the statistics, dO, Q^T image,
+  // dO^T image) that the loop spreads between its MFMAs: a burst of copy instructions holds
+  // up the issuing wavefronts until the texture path has taken them all.
+  auto fetch_piece = [&](int piece, int hg, int qt, char* stage, float* stat) {
     const int h = kvh * a.group + hg;
-    const int left = a.n_q - qt * kBQ;
-    const char* qp = qbase + (int64_t)h * a.q_hs * 2 + (int64_t)qt * q_tile_bytes;
-    const char* dp = dobase + (int64_t)h * 256 + (int64_t)qt * do_tile_bytes;
-    if (left >= kBQ) {
-      dma_tile_n<kCopies>(qp, qoff_full, stage, wave);
-      dma_tile_n<kCopies>(dp, dooff_full, stage + kTileBytes, wave);
-    } else {                                             // ragged last tile: rows past the end repeat the last row
-      dma_tile_n<kCopies>(qp, dma_n_offsets<kCopies>(a.q_ts, left, wave, lane), stage, wave);
-      dma_tile_n<kCopies>(dp, dma_n_offsets<kCopies>((int64_t)a.Hq * 128, left, wave, lane), stage + kTileBytes, wave);
+    if (piece < 2) {
+      const int left = a.n_q - qt * kBQ;                 // < kBQ: ragged last tile, rows past the end repeat the last row
+      if (piece == 0) {
+        const char* qp = qbase + (int64_t)h * a.q_hs * 2 + (int64_t)qt * q_tile_bytes;
+        if (left >= kBQ) dma_tile_n<kCopies>(qp, qoff_full, stage, wave);
+        else dma_tile_n<kCopies>(qp, dma_n_offsets<kCopies>(a.q_ts, left, wave, lane), stage, wave);
+        // statistics: even wavefronts fetch -LSE*log2e, odd ones delta (several fetch the same bytes)
+        const float* src = ((wave & 1) ? w.dl : w.nl2) + (int64_t)h * w.n_qtiles * kBQ + qt * kBQ + lane;
+        dma4(reinterpret_cast<const char*>(src), reinterpret_cast<char*>(stat + (wave & 1) * 64));
+      } else {
+        const char* dp = dobase + (int64_t)h * 256 + (int64_t)qt * do_tile_bytes;
+        if (left >= kBQ) dma_tile_n<kCopies>(dp, dooff_full, stage + kTileBytes, wave);
+        else dma_tile_n<kCopies>(dp, dma_n_offsets<kCopies>((int64_t)a.Hq * 128, left, wave, lane), stage + kTileBytes, wave);
+      }
+    } else {
+      const int64_t img = ((int64_t)h * w.n_qtiles + qt) * kImageBytes;
+      dma_tile_image<kCopies>((piece == 2 ? w.qt : w.dot) + img, stage + piece * kTileBytes, wave, lane);
     }
-    const int64_t img = ((int64_t)h * w.n_qtiles + qt) * kImageBytes;
-    dma_tile_image<kCopies>(w.qt + img, stage + 2 * kTileBytes, wave, lane);
-    dma_tile_image<kCopies>(w.dot + img, stage + 3 * kTileBytes, wave, lane);
-    // statistics: even wavefronts fetch -LSE*log2e, odd ones delta (several fetch the same bytes)
-    const float* src = ((wave & 1) ? w.dl : w.nl2) + (int64_t)h * w.n_qtiles * kBQ + qt * kBQ + lane;
-    dma4(reinterpret_cast<const char*>(src), reinterpret_cast<char*>(stat + (wave & 1) * 64));
   };
-  if (niter > 0) fetch(0, qt0, stage0, stat0);
+  if (niter > 0) {
+#pragma unroll
+    for (int piece = 0; piece < 4; ++piece) fetch_piece(piece, 0, qt0, stage0, stat0);
+  }
 
   // K (P role) or V (D role) rows of this lane's key as B operands (k index along d)
   u32x4 kvreg[8];
@@ -133,12 +141,13 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   for (int x = 0; x < 4; ++x) ta[x] = tile_t_offset(col, x * 2 + half) + (role_p ? 3 : 2) * kTileBytes;             // + db*4096
   char* const my_px = pxch + pair * 2048 + lane * 32;    // + slot * 8192
 
-  // (head of the group, query tile) of the tile being computed and of the next one to fetch,
-  // which runs two tiles ahead: both stages are filled before the loop starts.
+  // (head of the group, query tile) of the tile being computed and of the tile whose copies
+  // are being issued.  While tile t is computed: the rest of tile t+1 during its first block,
+  // the first piece of tile t+2 after its second barrier, which frees the stage of tile t.
   int cur_qt = qt0, f_hg = 0, f_qt = qt0;
   auto advance = [&](int& hg, int& qt) { if (++qt > qt1) { qt = qt0; ++hg; } };
   if (niter > 0) advance(f_hg, f_qt);
-  if (niter > 1) { fetch(f_hg, f_qt, stage1, stat1); advance(f_hg, f_qt); }
+  if (niter > 1) fetch_piece(0, f_hg, f_qt, stage1, stat1);
 
   // LDS operands are fetched a whole product ahead of the MFMAs that use them.  o1 feeds a
   // block's first product (S or dP); it is reloaded for the next block as soon as the MFMAs
@@ -157,7 +166,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   // so far.  The second barrier of a tile therefore also retires the tile's stage, which is
   // refilled at once with the tile after next, and publishes the next tile's stage (each
   // wavefront waits for its own copies of it first).
-  auto tile_body = [&](int it, char* cur, float* stat, const char* oth) {
+  auto tile_body = [&](int it, char* cur, float* stat, char* oth, float* ostat) {
     const int q0 = cur_qt * kBQ;
     if (++cur_qt > qt1) cur_qt = qt0;
     const bool need_mask = kMask && (q0 < w_lo_max || q0 + kBQ - 1 > w_hi_min);
@@ -168,7 +177,13 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
 #pragma unroll
       for (int i = 0; i < 16; ++i) x[i] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) x = mfma32(o1[ks], kvreg[ks], x);
+      for (int ks = 0; ks < 8; ++ks) {
+        x = mfma32(o1[ks], kvreg[ks], x);
+        if (qb == 0 && (ks == 2 || ks == 5)) {
+          if (it + 1 < niter) fetch_piece(ks == 2 ? 1 : 2, f_hg, f_qt, oth, ostat);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
         o2[2 * db] = *reinterpret_cast<const u32x4*>(cur + ta[(qb * 2) ^ db] + db * 4096);
@@ -216,8 +231,6 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
       } else {
         __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): own copies of the next tile
         lds_barrier_after_write();
-        if (it + 2 < niter) fetch(f_hg, f_qt, cur, stat);
-        advance(f_hg, f_qt);
         if (it + 1 < niter) {
 #pragma unroll
           for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(oth + na[ks]);
@@ -244,6 +257,15 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
       for (int db = 0; db < 4; ++db) {
         acc[db] = mfma32(o2[2 * db], b0, acc[db]);
         acc[db] = mfma32(o2[2 * db + 1], b1, acc[db]);
+        if (db == 1) {
+          if (qb == 0) {
+            if (it + 1 < niter) fetch_piece(3, f_hg, f_qt, oth, ostat);
+            advance(f_hg, f_qt);
+          } else if (it + 2 < niter) {
+            fetch_piece(0, f_hg, f_qt, cur, stat);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
   };
@@ -252,10 +274,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   // that no accumulator crosses a conditional inside the loop.
   int it = 0;
   for (; it + 1 < niter; it += 2) {
-    tile_body(it, stage0, stat0, stage1);
-    tile_body(it + 1, stage1, stat1, stage0);
+    tile_body(it, stage0, stat0, stage1, stat1);
+    tile_body(it + 1, stage1, stat1, stage0, stat0);
   }
-  if (it < niter) tile_body(it, stage0, stat0, stage1);
+  if (it < niter) tile_body(it, stage0, stat0, stage1, stat1);
 
   if (!live) return;
   const int64_t off = ((int64_t)(a.k_row0 + key) * a.Hkv + kvh) * 128 + half * 4;

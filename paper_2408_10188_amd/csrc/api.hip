@@ -92,9 +92,9 @@ mmsp_status device_result(hipError_t e, const char* what) {
 
 // bf16 kernels read token-contiguous operands from pre-transposed tile images (16 KiB per 64
 // rows and head) that each call builds in the workspace: V^T for the forward; Q^T, dO^T and the
-// padded row statistics for the backward.
+// padded row statistics (dK/dV kernel) plus K^T (dQ kernel) for the backward.
 size_t needed_workspace(const mmsp_shape* s, int64_t n_q, int64_t n_k, bool backward) {
-  if (backward) return (size_t)mmsp::bwd_bf16_workspace_bytes(s->n_q_heads, n_q);
+  if (backward) return (size_t)mmsp::bwd_bf16_total_workspace_bytes(s->n_q_heads, s->n_kv_heads, n_q, n_k);
   return (size_t)(s->n_kv_heads * mmsp::tiles_of(n_k) * mmsp::kImageBytes);
 }
 

@@ -87,33 +87,54 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   const int64_t q_tile_bytes = (int64_t)kBQ * a.q_ts * 2, do_tile_bytes = (int64_t)kBQ * a.Hq * 256;
   const DmaOffs<kCopies> qoff_full = dma_n_offsets<kCopies>(a.q_ts, kBQ, wave, lane);
   const DmaOffs<kCopies> dooff_full = dma_n_offsets<kCopies>((int64_t)a.Hq * 128, kBQ, wave, lane);
+  // Cursor over the (head of the group, query tile) sequence: byte offsets of the tile in the
+  // four sources, advanced by additions so that the loop carries no 64-bit multiplies.
+  struct Cursor { int qt; int64_t q, d_o, img, st; };
+  const int64_t q_head_step = (int64_t)a.q_hs * 2 - (int64_t)(ntiles - 1) * q_tile_bytes;
+  const int64_t do_head_step = 256 - (int64_t)(ntiles - 1) * do_tile_bytes;
+  const int64_t img_head_step = (int64_t)(w.n_qtiles - (ntiles - 1)) * kImageBytes;
+  const int64_t st_head_step = (int64_t)(w.n_qtiles - (ntiles - 1)) * kBQ * 4;
+  auto advance = [&](Cursor& cu) {
+    if (++cu.qt > qt1) {
+      cu.qt = qt0; cu.q += q_head_step; cu.d_o += do_head_step; cu.img += img_head_step; cu.st += st_head_step;
+    } else {
+      cu.q += q_tile_bytes; cu.d_o += do_tile_bytes; cu.img += kImageBytes; cu.st += kBQ * 4;
+    }
+  };
+  Cursor fc;                                             // tile whose copies are being issued
+  {
+    const int h0 = kvh * a.group;
+    fc.qt = qt0;
+    fc.q = (int64_t)h0 * a.q_hs * 2 + (int64_t)qt0 * q_tile_bytes;
+    fc.d_o = (int64_t)h0 * 256 + (int64_t)qt0 * do_tile_bytes;
+    fc.img = ((int64_t)h0 * w.n_qtiles + qt0) * kImageBytes;
+    fc.st = ((int64_t)h0 * w.n_qtiles + qt0) * kBQ * 4;
+  }
   // The copies of one tile are issued in four pieces (Q with the statistics, dO, Q^T image,
   // dO^T image) that the loop spreads between its MFMAs: a burst of copy instructions holds
   // up the issuing wavefronts until the texture path has taken them all.
-  auto fetch_piece = [&](int piece, int hg, int qt, char* stage, float* stat) {
-    const int h = kvh * a.group + hg;
+  const char* const stat_src = reinterpret_cast<const char*>((wave & 1) ? w.dl : w.nl2) + lane * 4;
+  auto fetch_piece = [&](int piece, const Cursor& cu, char* stage, float* stat) {
     if (piece < 2) {
-      const int left = a.n_q - qt * kBQ;                 // < kBQ: ragged last tile, rows past the end repeat the last row
+      const int left = a.n_q - cu.qt * kBQ;              // < kBQ: ragged last tile, rows past the end repeat the last row
       if (piece == 0) {
-        const char* qp = qbase + (int64_t)h * a.q_hs * 2 + (int64_t)qt * q_tile_bytes;
+        const char* qp = qbase + cu.q;
         if (left >= kBQ) dma_tile_n<kCopies>(qp, qoff_full, stage, wave);
         else dma_tile_n<kCopies>(qp, dma_n_offsets<kCopies>(a.q_ts, left, wave, lane), stage, wave);
         // statistics: even wavefronts fetch -LSE*log2e, odd ones delta (several fetch the same bytes)
-        const float* src = ((wave & 1) ? w.dl : w.nl2) + (int64_t)h * w.n_qtiles * kBQ + qt * kBQ + lane;
-        dma4(reinterpret_cast<const char*>(src), reinterpret_cast<char*>(stat + (wave & 1) * 64));
+        dma4(stat_src + cu.st, reinterpret_cast<char*>(stat + (wave & 1) * 64));
       } else {
-        const char* dp = dobase + (int64_t)h * 256 + (int64_t)qt * do_tile_bytes;
+        const char* dp = dobase + cu.d_o;
         if (left >= kBQ) dma_tile_n<kCopies>(dp, dooff_full, stage + kTileBytes, wave);
         else dma_tile_n<kCopies>(dp, dma_n_offsets<kCopies>((int64_t)a.Hq * 128, left, wave, lane), stage + kTileBytes, wave);
       }
     } else {
-      const int64_t img = ((int64_t)h * w.n_qtiles + qt) * kImageBytes;
-      dma_tile_image<kCopies>((piece == 2 ? w.qt : w.dot) + img, stage + piece * kTileBytes, wave, lane);
+      dma_tile_image<kCopies>((piece == 2 ? w.qt : w.dot) + cu.img, stage + piece * kTileBytes, wave, lane);
     }
   };
   if (niter > 0) {
 #pragma unroll
-    for (int piece = 0; piece < 4; ++piece) fetch_piece(piece, 0, qt0, stage0, stat0);
+    for (int piece = 0; piece < 4; ++piece) fetch_piece(piece, fc, stage0, stat0);
   }
 
   // K (P role) or V (D role) rows of this lane's key as B operands (k index along d)
@@ -144,10 +165,9 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   // (head of the group, query tile) of the tile being computed and of the tile whose copies
   // are being issued.  While tile t is computed: the rest of tile t+1 during its first block,
   // the first piece of tile t+2 after its second barrier, which frees the stage of tile t.
-  int cur_qt = qt0, f_hg = 0, f_qt = qt0;
-  auto advance = [&](int& hg, int& qt) { if (++qt > qt1) { qt = qt0; ++hg; } };
-  if (niter > 0) advance(f_hg, f_qt);
-  if (niter > 1) fetch_piece(0, f_hg, f_qt, stage1, stat1);
+  int cur_qt = qt0;
+  if (niter > 0) advance(fc);
+  if (niter > 1) fetch_piece(0, fc, stage1, stat1);
 
   // LDS operands are fetched a whole product ahead of the MFMAs that use them.  o1 feeds a
   // block's first product (S or dP); it is reloaded for the next block as soon as the MFMAs
@@ -180,7 +200,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
       for (int ks = 0; ks < 8; ++ks) {
         x = mfma32(o1[ks], kvreg[ks], x);
         if (qb == 0 && (ks == 2 || ks == 5)) {
-          if (it + 1 < niter) fetch_piece(ks == 2 ? 1 : 2, f_hg, f_qt, oth, ostat);
+          if (it + 1 < niter) fetch_piece(ks == 2 ? 1 : 2, fc, oth, ostat);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -259,10 +279,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
         acc[db] = mfma32(o2[2 * db + 1], b1, acc[db]);
         if (db == 1) {
           if (qb == 0) {
-            if (it + 1 < niter) fetch_piece(3, f_hg, f_qt, oth, ostat);
-            advance(f_hg, f_qt);
+            if (it + 1 < niter) fetch_piece(3, fc, oth, ostat);
+            advance(fc);
           } else if (it + 2 < niter) {
-            fetch_piece(0, f_hg, f_qt, cur, stat);
+            fetch_piece(0, fc, cur, stat);
           }
           __builtin_amdgcn_sched_barrier(0);
         }

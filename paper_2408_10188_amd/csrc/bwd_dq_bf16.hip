@@ -1,0 +1,212 @@
+// Backward ring step, dQ kernel (query-stationary) on bf16 matrix cores, head_dim 128.
+//
+// Same skeleton as the forward kernel: a workgroup is 8 wavefronts = 256 query rows of one
+// head, two wavefronts per SIMD; wavefront w owns 32 rows and keeps their Q and dO (MFMA B
+// operands), the dQ^T accumulator (128 d x 32 queries) and the two row statistics (-LSE*log2e,
+// delta) in registers for the whole call.  64-key tiles of K, V (natural orientation) and the
+// pre-transposed K^T tile image stream through a three-stage LDS ring filled by asynchronous
+// global->LDS copies.
+//   S^T[key][query]  = K . Q^T            P^T = exp2(S^T * c - LSE*log2e)   (final LSE: no running max)
+//   dP^T[key][query] = V . dO^T           dS^T = P^T * (dP^T - delta)
+//   dQ^T[d][query]  += K^T . dS^T         (B operand = dS^T straight from registers)
+// S and dP are recomputed here although the dK/dV kernel computes them too: that buys exclusive
+// ownership of dQ, hence no floating-point atomics and bit-reproducible results.
+#include "mfma_tiles.h"
+
+namespace mmsp {
+namespace {
+
+constexpr int kWaves = 8;
+constexpr int kBM = 32 * kWaves;   // query rows per workgroup
+constexpr int kBN = 64;            // keys per tile
+constexpr int kCopies = 16 / kWaves;
+constexpr int kStageBytes = 3 * kTileBytes;   // K TileN | V TileN | K^T TileT
+
+__global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a, const char* kt_images, int n_qt,
+                                                                     int xcd_per_kv) {
+  __shared__ __attribute__((aligned(1024))) char stage0[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char stage1[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) char stage2[kStageBytes];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, col = lane & 31;
+
+  // workgroup -> (head, query tile): the workgroups of a KV head share an XCD, later (heavier
+  // under the causal mask) query tiles first
+  int h, qt;
+  if (xcd_per_kv > 0) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int kvh0 = xcd / xcd_per_kv;
+    const int item = slot * xcd_per_kv + (xcd % xcd_per_kv);
+    if (item >= a.group * n_qt) return;
+    h = kvh0 * a.group + item % a.group;
+    qt = n_qt - 1 - item / a.group;
+  } else {
+    h = blockIdx.x % a.Hq;
+    qt = n_qt - 1 - blockIdx.x / a.Hq;
+  }
+  const int kvh = h / a.group;
+  const int tile_row0 = qt * kBM;
+  const int row = tile_row0 + wave * 32 + col;          // block-relative query row of this lane
+  const bool live = row < a.n_q;
+  const int rowc = min(row, a.n_q - 1);
+
+  int lo, hi;
+  key_interval_of_row(a, rowc, lo, hi);
+  int t_lo, t_hi, dummy;
+  key_interval_of_row(a, tile_row0, t_lo, dummy);
+  key_interval_of_row(a, min(tile_row0 + kBM, a.n_q) - 1, dummy, t_hi);
+  int w_lo_max, w_hi_min;                               // wavefront: largest lo, smallest hi
+  {
+    const int wr0 = min(tile_row0 + wave * 32, a.n_q - 1), wr1 = min(tile_row0 + wave * 32 + 31, a.n_q - 1);
+    key_interval_of_row(a, wr0, dummy, w_hi_min);
+    key_interval_of_row(a, wr1, w_lo_max, dummy);
+  }
+  const int kt0 = t_lo / kBN, kt1 = t_hi >= t_lo ? t_hi / kBN : kt0 - 1;   // inclusive tile range
+
+  // ---- asynchronous tile fetch ----
+  const int64_t kv_off = ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
+  const char* kbase = reinterpret_cast<const char*>(a.k) + kv_off;
+  const char* vbase = reinterpret_cast<const char*>(a.v) + kv_off;
+  const char* kimg = kt_images + (int64_t)kvh * tiles_of(a.n_k) * kImageBytes;
+  const int64_t tile_bytes = (int64_t)kBN * a.kv_ts * 2;
+  const DmaOffs<kCopies> off_full = dma_n_offsets<kCopies>(a.kv_ts, kBN, wave, lane);
+  auto fetch = [&](int kt, char* stage) {
+    const int left = a.n_k - kt * kBN;
+    const int64_t t = (int64_t)kt * tile_bytes;
+    if (left >= kBN) {
+      dma_tile_n<kCopies>(kbase + t, off_full, stage, wave);
+      dma_tile_n<kCopies>(vbase + t, off_full, stage + kTileBytes, wave);
+    } else {                                            // ragged last tile: rows past the end repeat the last row
+      const DmaOffs<kCopies> off = dma_n_offsets<kCopies>(a.kv_ts, left, wave, lane);
+      dma_tile_n<kCopies>(kbase + t, off, stage, wave);
+      dma_tile_n<kCopies>(vbase + t, off, stage + kTileBytes, wave);
+    }
+    dma_tile_image<kCopies>(kimg + (int64_t)kt * kImageBytes, stage + 2 * kTileBytes, wave, lane);
+  };
+  if (kt0 <= kt1) fetch(kt0, stage0);
+  if (kt0 + 1 <= kt1) fetch(kt0 + 1, stage1);
+
+  // Q and dO as B operands: k-step ks covers d = ks*16 .. +16, this lane holds 8 of them
+  const int64_t r = a.q_row0 + rowc;
+  u32x4 qreg[8], doreg[8];
+  {
+    const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q) + r * a.q_ts + (int64_t)h * a.q_hs + half * 8;
+    const uint16_t* dp = reinterpret_cast<const uint16_t*>(a.d_o) + (r * a.Hq + h) * 128 + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      qreg[ks] = *reinterpret_cast<const u32x4*>(qp + ks * 16);
+      doreg[ks] = *reinterpret_cast<const u32x4*>(dp + ks * 16);
+    }
+  }
+  const float L = a.lse_final[(int64_t)h * a.lse_hs + r];
+  const float Dl = a.delta[(int64_t)h * a.lse_hs + r];
+  const float neg_l2 = L == -INFINITY ? -INFINITY : -L * kLog2e;   // a row that saw nothing: P = 0
+  const float c = a.scale * kLog2e;
+
+  f32x16 dq[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
+
+  // LDS read offsets inside a stage, fixed for the whole call: K / V operand k-step ks (rows
+  // +32 -> +8192 bytes, V tile +16 KiB), K^T operand chunk pair x = g ^ db (d block db -> +4096)
+  int ka[8], ta[4];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) ka[ks] = tile_n_offset(col, ks * 2 + half);
+#pragma unroll
+  for (int x = 0; x < 4; ++x) ta[x] = 2 * kTileBytes + tile_t_offset(col, x * 2 + half);
+
+  auto tile_body = [&](int kt, const char* cur, char* refill) {
+    // Own copies of tile kt have landed (the newest tile's may still be in flight); after the
+    // barrier everybody's have, and everybody is done with the stage about to be refilled.
+    if (kt < kt1) __builtin_amdgcn_s_waitcnt(0x0F70 | (3 * kCopies)); else __builtin_amdgcn_s_waitcnt(0x0F70);
+    lds_barrier();
+    if (kt + 2 <= kt1) fetch(kt + 2, refill);
+    const int k0 = kt * kBN;
+    const bool need_mask = k0 < w_lo_max || k0 + kBN - 1 > w_hi_min;
+
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        s = mfma32(*reinterpret_cast<const u32x4*>(cur + ka[ks] + kb * 8192), qreg[ks], s);
+        dp = mfma32(*reinterpret_cast<const u32x4*>(cur + kTileBytes + ka[ks] + kb * 8192), doreg[ks], dp);
+      }
+      // K^T operands of the third product: issued now, they land during the exp / dS arithmetic
+      u32x4 top[8];
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        top[2 * db] = *reinterpret_cast<const u32x4*>(cur + ta[(kb * 2) ^ db] + db * 4096);
+        top[2 * db + 1] = *reinterpret_cast<const u32x4*>(cur + ta[(kb * 2 + 1) ^ db] + db * 4096);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (need_mask) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = k0 + kb * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
+          s[i] = (key < lo || key > hi) ? -INFINITY : s[i];
+        }
+      }
+      uint32_t w[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[2 * j], c, neg_l2));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[2 * j + 1], c, neg_l2));
+        w[j] = pack2(p0 * (dp[2 * j] - Dl), p1 * (dp[2 * j + 1] - Dl));
+      }
+      const u32x4 b0 = mk4(w[0], w[1], w[2], w[3]);
+      const u32x4 b1 = mk4(w[4], w[5], w[6], w[7]);
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        dq[db] = mfma32(top[2 * db], b0, dq[db]);
+        dq[db] = mfma32(top[2 * db + 1], b1, dq[db]);
+      }
+    }
+  };
+
+  // Three bodies per trip so that every LDS offset is a compile-time constant.
+  for (int kt = kt0; kt <= kt1; kt += 3) {
+    tile_body(kt, stage0, stage2);
+    if (kt + 1 <= kt1) tile_body(kt + 1, stage1, stage0);
+    if (kt + 2 <= kt1) tile_body(kt + 2, stage2, stage1);
+  }
+
+  if (!live) return;
+  float* out = a.dq + ((int64_t)(a.q_row0 + row) * a.Hq + h) * 128 + half * 4;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      float4* dst = reinterpret_cast<float4*>(out + db * 32 + g4 * 8);
+      float4 o = *dst;
+      o.x += a.scale * dq[db][g4 * 4 + 0]; o.y += a.scale * dq[db][g4 * 4 + 1];
+      o.z += a.scale * dq[db][g4 * 4 + 2]; o.w += a.scale * dq[db][g4 * 4 + 3];
+      *dst = o;
+    }
+}
+
+}  // namespace
+
+int64_t bwd_dq_bf16_workspace_bytes(int Hkv, int64_t n_k) { return (int64_t)Hkv * tiles_of(n_k) * kImageBytes; }
+
+// kt_images: room for bwd_dq_bf16_workspace_bytes(Hkv, n_k) bytes, filled here with the K^T
+// tile images of the visiting block.
+hipError_t launch_bwd_dq_bf16(const StepArgs& a, char* kt_images, hipStream_t stream) {
+  hipError_t e = launch_transpose_tiles(a.k, a.kv_ts, a.kv_hs, a.Hkv, a.k_row0, a.n_k, kt_images, stream);
+  if (e != hipSuccess) return e;
+  const int n_qt = (a.n_q + kBM - 1) / kBM;
+  int xcd_per_kv = 0, n_blocks = n_qt * a.Hq;
+  if (8 % a.Hkv == 0) {
+    xcd_per_kv = 8 / a.Hkv;
+    n_blocks = 8 * ((a.group * n_qt + xcd_per_kv - 1) / xcd_per_kv);
+  }
+  bwd_dq_bf16_kernel<<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, kt_images, n_qt, xcd_per_kv);
+  return hipGetLastError();
+}
+
+}  // namespace mmsp

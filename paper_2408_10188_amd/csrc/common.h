@@ -104,6 +104,9 @@ hipError_t launch_bwd_stats(const float* lse, const float* delta, int64_t lse_hs
                             float* nl2, float* dl, hipStream_t stream);
 hipError_t launch_bwd_dkdv_bf16(const StepArgs& a, const BwdWorkspace& w, hipStream_t stream);
 int64_t bwd_bf16_workspace_bytes(int Hq, int64_t n_q);
+hipError_t launch_bwd_dq_bf16(const StepArgs& a, char* kt_images, hipStream_t stream);
+int64_t bwd_dq_bf16_workspace_bytes(int Hkv, int64_t n_k);
+int64_t bwd_bf16_total_workspace_bytes(int Hq, int Hkv, int64_t n_q, int64_t n_k);
 hipError_t bwd_bf16_prepare(const StepArgs& a, BwdWorkspace& w, hipStream_t stream);
 
 hipError_t launch_fwd_f32(const StepArgs& a, hipStream_t stream);

@@ -32,8 +32,12 @@ __device__ __forceinline__ void dma4(const char* gptr, char* lds_wave_base) {
 
 // kMask = false: the host has checked that every (query, key) pair of the block is visible and
 // that n_q is a multiple of the tile length, so no tile needs masking.
+// nsplit > 1: the (head, query tile) sequence of every key tile is cut into nsplit contiguous
+// ranges, one workgroup each, which store their partial dK / dV into w.partial for
+// dkdv_reduce_kernel to sum (used when one workgroup per key tile would leave CUs idle).
 template <bool kMask>
-__global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWorkspace w, int n_kt, int xcd_per_kv) {
+__global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWorkspace w, int n_kt, int xcd_per_kv,
+                                                                       int nsplit) {
   __shared__ __attribute__((aligned(1024))) char stage0[kStage];
   __shared__ __attribute__((aligned(1024))) char stage1[kStage];
   __shared__ __attribute__((aligned(1024))) float stat0[128];      // [0,64) -LSE*log2e, [64,128) delta
@@ -45,16 +49,17 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   const int pair = wave & 3;                    // which 32 keys
   const bool role_p = wave < 4;                 // true: S / P / dV,  false: dP / dS / dK
 
-  int kvh, kt;
+  int kvh, item;                    // item = key tile * nsplit + range
   if (xcd_per_kv > 0) {             // workgroups of one KV head share an XCD (its L2 then serves the Q/dO stream once)
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     kvh = xcd / xcd_per_kv;
-    kt = slot * xcd_per_kv + (xcd % xcd_per_kv);
-    if (kt >= n_kt) return;
+    item = slot * xcd_per_kv + (xcd % xcd_per_kv);
+    if (item >= n_kt * nsplit) return;
   } else {
-    kvh = blockIdx.x / n_kt;
-    kt = blockIdx.x % n_kt;
+    kvh = blockIdx.x / (n_kt * nsplit);
+    item = blockIdx.x % (n_kt * nsplit);
   }
+  const int kt = item / nsplit, split = item % nsplit;
   const int tile_key0 = kt * kKeys;
   const int key = tile_key0 + pair * 32 + col;           // block-relative key of this lane
   const bool live = key < a.n_k;
@@ -79,7 +84,14 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   w_hi_min = __builtin_amdgcn_readfirstlane(w_hi_min);
   const int qt0 = t_lo / kBQ, qt1 = t_hi >= t_lo ? t_hi / kBQ : qt0 - 1;
   const int ntiles = qt1 - qt0 + 1;
-  const int niter = ntiles > 0 ? ntiles * a.group : 0;
+  // this workgroup's range [it0, it0 + niter) of the (head of the group, query tile) sequence
+  int it0 = 0, niter = 0;
+  if (ntiles > 0) {
+    const int total = ntiles * a.group;
+    it0 = (int)((int64_t)total * split / nsplit);
+    niter = (int)((int64_t)total * (split + 1) / nsplit) - it0;
+  }
+  const int hg_first = ntiles > 0 ? it0 / ntiles : 0, qt_first = ntiles > 0 ? qt0 + it0 % ntiles : qt0;
 
   // ---- asynchronous tile fetch (all 8 wavefronts share the copies) ----
   const char* qbase = reinterpret_cast<const char*>(a.q) + (int64_t)a.q_row0 * a.q_ts * 2;
@@ -103,12 +115,12 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   };
   Cursor fc;                                             // tile whose copies are being issued
   {
-    const int h0 = kvh * a.group;
-    fc.qt = qt0;
-    fc.q = (int64_t)h0 * a.q_hs * 2 + (int64_t)qt0 * q_tile_bytes;
-    fc.d_o = (int64_t)h0 * 256 + (int64_t)qt0 * do_tile_bytes;
-    fc.img = ((int64_t)h0 * w.n_qtiles + qt0) * kImageBytes;
-    fc.st = ((int64_t)h0 * w.n_qtiles + qt0) * kBQ * 4;
+    const int h0 = kvh * a.group + hg_first;
+    fc.qt = qt_first;
+    fc.q = (int64_t)h0 * a.q_hs * 2 + (int64_t)qt_first * q_tile_bytes;
+    fc.d_o = (int64_t)h0 * 256 + (int64_t)qt_first * do_tile_bytes;
+    fc.img = ((int64_t)h0 * w.n_qtiles + qt_first) * kImageBytes;
+    fc.st = ((int64_t)h0 * w.n_qtiles + qt_first) * kBQ * 4;
   }
   // The copies of one tile are issued in four pieces (Q with the statistics, dO, Q^T image,
   // dO^T image) that the loop spreads between its MFMAs: a burst of copy instructions holds
@@ -165,7 +177,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   // (head of the group, query tile) of the tile being computed and of the tile whose copies
   // are being issued.  While tile t is computed: the rest of tile t+1 during its first block,
   // the first piece of tile t+2 after its second barrier, which frees the stage of tile t.
-  int cur_qt = qt0;
+  int cur_qt = qt_first;
   if (niter > 0) advance(fc);
   if (niter > 1) fetch_piece(0, fc, stage1, stat1);
 
@@ -300,9 +312,20 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   if (it < niter) tile_body(it, stage0, stat0, stage1, stat1);
 
   if (!live) return;
+  const float mul = role_p ? 1.f : a.scale;
+  if (nsplit > 1) {                                      // partial result of this range, summed by dkdv_reduce_kernel
+    const int64_t slot_elems = (int64_t)n_kt * kKeys * a.Hkv * 128;
+    float* out = w.partial + ((int64_t)(role_p ? nsplit : 0) + split) * slot_elems + ((int64_t)key * a.Hkv + kvh) * 128 + half * 4;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4)
+        *reinterpret_cast<float4*>(out + db * 32 + g4 * 8) =
+            make_float4(mul * acc[db][g4 * 4 + 0], mul * acc[db][g4 * 4 + 1], mul * acc[db][g4 * 4 + 2], mul * acc[db][g4 * 4 + 3]);
+    return;
+  }
   const int64_t off = ((int64_t)(a.k_row0 + key) * a.Hkv + kvh) * 128 + half * 4;
   float* out = (role_p ? a.dv : a.dk) + off;
-  const float mul = role_p ? 1.f : a.scale;
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -318,18 +341,60 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
     }
 }
 
+// out[i] (+)= sum over the nsplit partial slots, for the n4 float4 of dK (blockIdx.y = 0) or dV (1).
+__global__ __launch_bounds__(256) void dkdv_reduce_kernel(const float* __restrict__ partial, int nsplit, int64_t slot_elems,
+                                                          float* __restrict__ dk, float* __restrict__ dv, int64_t n4,
+                                                          bool accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  const float* src = partial + (int64_t)blockIdx.y * nsplit * slot_elems + i * 4;
+  float4* dst = reinterpret_cast<float4*>(blockIdx.y ? dv : dk) + i;
+  float4 x = accumulate ? *dst : make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int sidx = 0; sidx < nsplit; ++sidx) {
+    const float4 p = *reinterpret_cast<const float4*>(src + sidx * slot_elems);
+    x.x += p.x; x.y += p.y; x.z += p.z; x.w += p.w;
+  }
+  *dst = x;
+}
+
 }  // namespace
+
+// Workgroups the partial-sum area is sized for: ranges are only cut while (key tiles x KV
+// heads x ranges) stays within this count.
+constexpr int kSplitMaxBlocks = 256;
+constexpr int kSplitMaxRanges = 8;
+
+int64_t bwd_dkdv_partial_bytes() { return 2LL * kSplitMaxBlocks * kKeys * 128 * (int64_t)sizeof(float); }
 
 hipError_t launch_bwd_dkdv_bf16(const StepArgs& a, const BwdWorkspace& w, hipStream_t stream) {
   const int n_kt = (a.n_k + kKeys - 1) / kKeys;
-  int xcd_per_kv = 0, n_blocks = n_kt * a.Hkv;
+  // One workgroup per (key tile, KV head) fills the chip only if there are about as many as
+  // CUs; with fewer, cut every key tile's query sequence into ranges.
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = kSplitMaxBlocks;
+    n_cu = v;
+  }
+  const int base_blocks = n_kt * a.Hkv;
+  int nsplit = min(min(n_cu, kSplitMaxBlocks) / base_blocks, kSplitMaxRanges);
+  if (nsplit < 2) nsplit = 1;
+  const int n_items = n_kt * nsplit;
+  int xcd_per_kv = 0, n_blocks = n_items * a.Hkv;
   if (8 % a.Hkv == 0) {
     xcd_per_kv = 8 / a.Hkv;
-    n_blocks = 8 * ((n_kt + xcd_per_kv - 1) / xcd_per_kv);
+    n_blocks = 8 * ((n_items + xcd_per_kv - 1) / xcd_per_kv);
   }
   const bool no_mask = a.mask == 0 && a.cu == nullptr && a.n_q % kBQ == 0;
-  if (no_mask) bwd_dkdv_bf16_kernel<false><<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, w, n_kt, xcd_per_kv);
-  else bwd_dkdv_bf16_kernel<true><<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, w, n_kt, xcd_per_kv);
+  if (no_mask) bwd_dkdv_bf16_kernel<false><<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, w, n_kt, xcd_per_kv, nsplit);
+  else bwd_dkdv_bf16_kernel<true><<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, w, n_kt, xcd_per_kv, nsplit);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || nsplit == 1) return e;
+  const int64_t n4 = (int64_t)a.n_k * a.Hkv * 32;
+  const int64_t first = (int64_t)a.k_row0 * a.Hkv * 128;
+  dkdv_reduce_kernel<<<dim3((unsigned)((n4 + 255) / 256), 2), dim3(256), 0, stream>>>(
+      w.partial, nsplit, (int64_t)n_kt * kKeys * a.Hkv * 128, a.dk + first, a.dv + first, n4, a.accumulate);
   return hipGetLastError();
 }
 

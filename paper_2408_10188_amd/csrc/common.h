@@ -37,6 +37,7 @@ struct BwdWorkspace {
   const char* dot;     // dO^T tile images  [Hq][n_qtiles][16 KiB]
   const float* nl2;    // -LSE*log2e, [Hq][n_qtiles*64], -inf where LSE = -inf and in the padding
   const float* dl;     // delta,      [Hq][n_qtiles*64], 0 in the padding
+  float* partial;      // partial dK then dV of split key tiles, bwd_dkdv_partial_bytes() in all
   int32_t n_qtiles;
 };
 
@@ -104,6 +105,7 @@ hipError_t launch_bwd_stats(const float* lse, const float* delta, int64_t lse_hs
                             float* nl2, float* dl, hipStream_t stream);
 hipError_t launch_bwd_dkdv_bf16(const StepArgs& a, const BwdWorkspace& w, hipStream_t stream);
 int64_t bwd_bf16_workspace_bytes(int Hq, int64_t n_q);
+int64_t bwd_dkdv_partial_bytes();
 hipError_t launch_bwd_dq_bf16(const StepArgs& a, char* kt_images, hipStream_t stream);
 int64_t bwd_dq_bf16_workspace_bytes(int Hkv, int64_t n_k);
 int64_t bwd_bf16_total_workspace_bytes(int Hq, int Hkv, int64_t n_q, int64_t n_k);

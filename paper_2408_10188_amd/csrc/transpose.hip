@@ -51,19 +51,19 @@ hipError_t launch_bwd_stats(const float* lse, const float* delta, int64_t lse_hs
 
 int64_t bwd_bf16_workspace_bytes(int Hq, int64_t n_q) {
   const int64_t t = tiles_of(n_q);
-  return 2 * Hq * t * kImageBytes + 2 * Hq * t * 64 * (int64_t)sizeof(float);
+  return 2 * Hq * t * kImageBytes + 2 * Hq * t * 64 * (int64_t)sizeof(float) + bwd_dkdv_partial_bytes();
 }
 
-// Lays out the workspace of one backward call and fills it: Q^T / dO^T tile images and the
-// padded row statistics.
+// Lays out the dK/dV kernel's part of the workspace of one backward call and fills it: Q^T /
+// dO^T tile images and the padded row statistics; the partial-sum area follows them.
 hipError_t bwd_bf16_prepare(const StepArgs& a, BwdWorkspace& w, hipStream_t stream) {
   const int64_t t = tiles_of(a.n_q);
   char* p = a.ws;
   char* qt = p;            p += a.Hq * t * kImageBytes;
   char* dot = p;           p += a.Hq * t * kImageBytes;
   float* nl2 = reinterpret_cast<float*>(p);  p += a.Hq * t * 64 * sizeof(float);
-  float* dl = reinterpret_cast<float*>(p);
-  w.qt = qt; w.dot = dot; w.nl2 = nl2; w.dl = dl; w.n_qtiles = (int32_t)t;
+  float* dl = reinterpret_cast<float*>(p);   p += a.Hq * t * 64 * sizeof(float);
+  w.qt = qt; w.dot = dot; w.nl2 = nl2; w.dl = dl; w.partial = reinterpret_cast<float*>(p); w.n_qtiles = (int32_t)t;
   hipError_t e = launch_transpose_tiles(a.q, a.q_ts, a.q_hs, a.Hq, a.q_row0, a.n_q, qt, stream);
   if (e != hipSuccess) return e;
   e = launch_transpose_tiles(a.d_o, (int64_t)a.Hq * 128, 128, a.Hq, a.q_row0, a.n_q, dot, stream);

@@ -31,12 +31,84 @@ def pairs_of_rank(N, C):
     return 2 * N * C * C + C
 
 
+def bench_ulysses(args, cfg, torch, np, B, ring, synth):
+    """Head-shard mode: one GPU's 7/1 heads over the whole packed sequence, document-causal mask
+    from cu_seqlens, one forward and one backward step."""
+    T, Hq, Hkv, d = 2 * cfg["C"], cfg["Hq"], cfg["Hkv"], cfg["d"]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    Cg = 8192
+
+    def gen(name, H, sig):
+        out = torch.empty(T, H, d, dtype=torch.bfloat16, device=dev)
+        for c in range(T // Cg):
+            x = synth.chunk(name, c, Cg, H, d, sig, cfg["seed"])
+            out[c * Cg:(c + 1) * Cg] = torch.from_numpy(synth.bf16_bits(x).view(np.int16)).view(torch.bfloat16).to(dev)
+        return out
+
+    q, k, v, d_o = gen("q", Hq, cfg["sigma"]), gen("k", Hkv, cfg["sigma"]), gen("v", Hkv, cfg["sigma"]), gen("do", Hq, 1.0)
+    cu = synth.packed_cu_seqlens(T, cfg["seed"])
+    cud = torch.from_numpy(cu).to(dev)
+    n_docs = len(cu) - 1
+    shape = ring.shape_for(q, k, B.MMSP_BF16, T, 1.0 / math.sqrt(d))
+    o_acc = torch.empty(T, Hq, d, dtype=torch.float32, device=dev)
+    lse = torch.empty(Hq, T, dtype=torch.float32, device=dev)
+    o_final, delta, dq = torch.empty_like(q), torch.empty_like(lse), torch.zeros_like(o_acc)
+    dk = torch.zeros(T, Hkv, d, dtype=torch.float32, device=dev)
+    dv = torch.zeros_like(dk)
+    ws_bytes = ring.workspace_bytes(shape, T, T)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    side = None
+    if not args.one_stream:      # dQ and dK/dV kernels on two streams (the side lane's accumulators are not used here)
+        side = ring.SideLane(torch.cuda.Stream(), None, None, torch.empty_like(ws), ws_bytes)
+
+    def fwd():
+        ring.ulysses_forward(shape, T, q, k, v, cud, n_docs, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes)
+
+    def bwd():
+        dq.zero_()
+        ring.ulysses_backward(shape, T, q, k, v, cud, n_docs, o_final, d_o, lse, delta, dq, dk, dv, ws=ws, ws_bytes=ws_bytes,
+                              side=side)
+
+    for _ in range(args.warmup):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+    lens = np.diff(cu).astype(np.int64)
+    pairs = int((lens * (lens + 1) // 2).sum())
+    flops = 14 * d * Hq * pairs
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    e[0].record(); fwd(); e[1].record(); bwd(); e[2].record()
+    torch.cuda.synchronize()
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    return {
+        "metric": "causal attention TFLOP/s fwd+bwd per rank shard; % of MI355X bf16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic", "frac_of_bf16_dense_peak": value / BF16_DENSE_PEAK_TFLOPS,
+        "config": {"workload": "ulysses: head shard %d/%d heads, d=%d, bf16, T=%d packed from %d documents (%d..%d tokens), "
+                               "document-causal mask, fwd+bwd in one step" % (Hq, Hkv, d, T, n_docs, lens.min(), lens.max()),
+                   "pairs_per_head": pairs, "tflop_fwd": 4 * d * Hq * pairs / 1e12, "tflop_bwd": 10 * d * Hq * pairs / 1e12},
+        "roofline": {"kernel": "fwd+bwd (all kernels of the step)", "bound": "mfma", "achieved": value,
+                     "peak": BF16_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": value / BF16_DENSE_PEAK_TFLOPS, "traffic": None},
+        "cpu_baseline": None,
+        "breakdown": {"fwd_ms": e[0].elapsed_time(e[1]), "bwd_ms": e[1].elapsed_time(e[2])},
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="long", choices=["cfg3", "long"])
+    ap.add_argument("--config", default="long", choices=["cfg3", "long", "ulysses"],
+                    help="long (default, the headline workload) and cfg3: one zigzag rank, fwd+bwd; ulysses: "
+                         "head-shard mode, 7/1 heads over the whole packed 256K sequence, fwd+bwd in one step")
     ap.add_argument("--rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--one-stream", action="store_true", help="all launches on one stream (no overlap of ring steps)")
@@ -64,6 +136,9 @@ def main():
         return
 
     cfg = synth.CONFIGS[args.config]
+    if args.config == "ulysses":
+        print(json.dumps(bench_ulysses(args, cfg, torch, np, B, ring, synth)))
+        return
     N, C, Hq, Hkv, d = cfg["N"], cfg["C"], cfg["Hq"], cfg["Hkv"], cfg["d"]
     T, n = 2 * N * C, 2 * C
     rank = args.rank

@@ -123,6 +123,18 @@ def ulysses_forward(shape, T, q, k, v, cu_seqlens, n_docs, o_acc, lse, o_final=N
 
 
 def ulysses_backward(shape, T, q, k, v, cu_seqlens, n_docs, o_final, d_o, lse, delta, dq, dk, dv, stream=0, ws=None,
-                     ws_bytes=0):
+                     ws_bytes=0, side=None):
+    """With `side` the dQ kernel runs on the current torch stream and the dK/dV kernel on side.stream."""
     blk = B.make_block(0, T, 0, T, B.MMSP_MASK_CAUSAL_DIAG, 0, 0, cu_seqlens, n_docs)
+    if side is not None:
+        import torch
+        main = torch.cuda.current_stream()
+        B.mmsp_attn_delta(shape, 0, T, o_final, d_o, delta, stream=main.cuda_stream)
+        side.stream.wait_stream(main)
+        B.mmsp_attn_step_bwd(shape, blk, q, k, v, None, d_o, lse, delta, False, dq, None, None, False, ws, ws_bytes,
+                             main.cuda_stream)
+        B.mmsp_attn_step_bwd(shape, blk, q, k, v, None, d_o, lse, delta, False, None, dk, dv, False, side.ws,
+                             side.ws_bytes, side.handle)
+        main.wait_stream(side.stream)
+        return
     B.mmsp_attn_step_bwd(shape, blk, q, k, v, o_final, d_o, lse, delta, True, dq, dk, dv, False, ws, ws_bytes, stream)

@@ -63,7 +63,7 @@ def test_config2_forward_all_ranks_sampled_rows():
 def test_config3_fwd_bwd_sampled_rows_and_keys(rank):
     prob = RankProblem(synth.CONFIGS["cfg3"])
     q, do = prob.rank_inputs(rank)
-    out = prob.run_gpu(rank, q, do)
+    out = prob.run_gpu(rank, q, do, two_streams=(rank == 0))   # both launch configurations
     _check_sampled_rows(prob, rank, out, q, do, _sample_rows(prob.C, 6, 200 + rank), backward=True)
     _check_column_sums(prob, out, do)
     if rank != 0:
@@ -91,7 +91,7 @@ def test_config3_fwd_bwd_sampled_rows_and_keys(rank):
 def test_long_shard_fwd_bwd_sampled_rows():
     prob = RankProblem(synth.CONFIGS["long"])
     q, do = prob.rank_inputs(0)
-    out = prob.run_gpu(0, q, do)
+    out = prob.run_gpu(0, q, do, two_streams=True)             # the launch configuration bench.py times
     _check_sampled_rows(prob, 0, out, q, do, _sample_rows(prob.C, 4, 300), backward=True)
     _check_column_sums(prob, out, do)
 
@@ -117,8 +117,9 @@ def test_ulysses_packed_fwd_bwd_sampled_rows():
     ws_bytes = ring.workspace_bytes(shape, T, T)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
     ring.ulysses_forward(shape, T, qd, kd, vd, cud, len(cu) - 1, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes)
+    side = ring.SideLane(torch.cuda.Stream(), None, None, torch.empty_like(ws), ws_bytes)   # dK/dV on a second stream, as bench.py runs it
     ring.ulysses_backward(shape, T, qd, kd, vd, cud, len(cu) - 1, o_final, dod, lse, delta, dq, dk, dv, ws=ws,
-                          ws_bytes=ws_bytes)
+                          ws_bytes=ws_bytes, side=side)
     torch.cuda.synchronize()
     # sampled rows: document starts, document ends, and random rows
     rows = np.unique(np.concatenate([cu[:-1], cu[1:] - 1, np.random.default_rng(5).choice(T, 10, replace=False)]))

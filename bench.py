@@ -113,6 +113,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--one-stream", action="store_true", help="all launches on one stream (no overlap of ring steps)")
     ap.add_argument("--cpu-rows", type=int, default=32, help="query rows per chunk in the oracle sample")
+    ap.add_argument("--ceiling", action="store_true",
+                    help="only run the stand-alone matrix-core ceiling probe (what MFMA + LDS + softmax-like work sustains "
+                         "with trivial and with random operands) and print its lines")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -120,6 +123,14 @@ def main():
         print("bench.py measures one GPU's share of the ring (one rank); this build has no multi-GPU path: "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.ceiling:
+        import subprocess
+        probe = os.path.join(ROOT, "paper_2408_10188_amd", "ceiling_probe")
+        if not os.path.exists(probe):
+            print("ceiling_probe is not built: run __graft_entry__.build() first", file=sys.stderr)
+            sys.exit(1)
+        sys.exit(subprocess.run([probe]).returncode)
 
     import numpy as np
     import torch

@@ -91,7 +91,12 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
     it0 = (int)((int64_t)total * split / nsplit);
     niter = (int)((int64_t)total * (split + 1) / nsplit) - it0;
   }
-  const int hg_first = ntiles > 0 ? it0 / ntiles : 0, qt_first = ntiles > 0 ? qt0 + it0 % ntiles : qt0;
+  // Sequence order: query tiles from the last visible one downwards, the heads of the group
+  // inside a tile.  Under a causal or document mask the key tiles that share an XCD see query
+  // ranges with different starts but a common end, so walking down from the end keeps their
+  // workgroups on the same Q / dO tiles (served once from HBM, then from L2) for as long as
+  // their ranges overlap.
+  const int hg_first = it0 % a.group, qt_first = qt1 - it0 / a.group;
 
   // ---- asynchronous tile fetch (all 8 wavefronts share the copies) ----
   const char* qbase = reinterpret_cast<const char*>(a.q) + (int64_t)a.q_row0 * a.q_ts * 2;
@@ -101,22 +106,23 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   const DmaOffs<kCopies> dooff_full = dma_n_offsets<kCopies>((int64_t)a.Hq * 128, kBQ, wave, lane);
   // Cursor over the (head of the group, query tile) sequence: byte offsets of the tile in the
   // four sources, advanced by additions so that the loop carries no 64-bit multiplies.
-  struct Cursor { int qt; int64_t q, d_o, img, st; };
-  const int64_t q_head_step = (int64_t)a.q_hs * 2 - (int64_t)(ntiles - 1) * q_tile_bytes;
-  const int64_t do_head_step = 256 - (int64_t)(ntiles - 1) * do_tile_bytes;
-  const int64_t img_head_step = (int64_t)(w.n_qtiles - (ntiles - 1)) * kImageBytes;
-  const int64_t st_head_step = (int64_t)(w.n_qtiles - (ntiles - 1)) * kBQ * 4;
+  struct Cursor { int hg, qt; int64_t q, d_o, img, st; };
+  const int64_t q_head_step = (int64_t)a.q_hs * 2, do_head_step = 256;
+  const int64_t img_head_step = (int64_t)w.n_qtiles * kImageBytes, st_head_step = (int64_t)w.n_qtiles * kBQ * 4;
+  const int gm1 = a.group - 1;
   auto advance = [&](Cursor& cu) {
-    if (++cu.qt > qt1) {
-      cu.qt = qt0; cu.q += q_head_step; cu.d_o += do_head_step; cu.img += img_head_step; cu.st += st_head_step;
+    if (++cu.hg == a.group) {                            // next (lower) query tile, first head of the group
+      cu.hg = 0; --cu.qt;
+      cu.q -= gm1 * q_head_step + q_tile_bytes; cu.d_o -= gm1 * do_head_step + do_tile_bytes;
+      cu.img -= gm1 * img_head_step + kImageBytes; cu.st -= gm1 * st_head_step + kBQ * 4;
     } else {
-      cu.q += q_tile_bytes; cu.d_o += do_tile_bytes; cu.img += kImageBytes; cu.st += kBQ * 4;
+      cu.q += q_head_step; cu.d_o += do_head_step; cu.img += img_head_step; cu.st += st_head_step;
     }
   };
   Cursor fc;                                             // tile whose copies are being issued
   {
     const int h0 = kvh * a.group + hg_first;
-    fc.qt = qt_first;
+    fc.hg = hg_first; fc.qt = qt_first;
     fc.q = (int64_t)h0 * a.q_hs * 2 + (int64_t)qt_first * q_tile_bytes;
     fc.d_o = (int64_t)h0 * 256 + (int64_t)qt_first * do_tile_bytes;
     fc.img = ((int64_t)h0 * w.n_qtiles + qt_first) * kImageBytes;
@@ -177,7 +183,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   // (head of the group, query tile) of the tile being computed and of the tile whose copies
   // are being issued.  While tile t is computed: the rest of tile t+1 during its first block,
   // the first piece of tile t+2 after its second barrier, which frees the stage of tile t.
-  int cur_qt = qt_first;
+  int cur_hg = hg_first, cur_qt = qt_first;
   if (niter > 0) advance(fc);
   if (niter > 1) fetch_piece(0, fc, stage1, stat1);
 
@@ -200,7 +206,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   // wavefront waits for its own copies of it first).
   auto tile_body = [&](int it, char* cur, float* stat, char* oth, float* ostat) {
     const int q0 = cur_qt * kBQ;
-    if (++cur_qt > qt1) cur_qt = qt0;
+    if (++cur_hg == a.group) { cur_hg = 0; --cur_qt; }
     const bool need_mask = kMask && (q0 < w_lo_max || q0 + kBQ - 1 > w_hi_min);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {

@@ -367,7 +367,7 @@ __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const float* __restric
 
 // Workgroups the partial-sum area is sized for: ranges are only cut while (key tiles x KV
 // heads x ranges) stays within this count.
-constexpr int kSplitMaxBlocks = 256;
+constexpr int kSplitMaxBlocks = 512;
 constexpr int kSplitMaxRanges = 8;
 
 int64_t bwd_dkdv_partial_bytes() { return 2LL * kSplitMaxBlocks * kKeys * 128 * (int64_t)sizeof(float); }
@@ -383,8 +383,13 @@ hipError_t launch_bwd_dkdv_bf16(const StepArgs& a, const BwdWorkspace& w, hipStr
       v = kSplitMaxBlocks;
     n_cu = v;
   }
+  // With every pair visible all key tiles carry the same work and one round of workgroups is
+  // best; under a mask the work per key tile varies (by 2x across a causal block), so aim for
+  // two rounds of shorter workgroups, which the dispatcher then balances (heavy tiles come first).
+  const bool no_mask = a.mask == 0 && a.cu == nullptr && a.n_q % kBQ == 0;
   const int base_blocks = n_kt * a.Hkv;
-  int nsplit = min(min(n_cu, kSplitMaxBlocks) / base_blocks, kSplitMaxRanges);
+  const int target = min(no_mask ? n_cu : 2 * n_cu, kSplitMaxBlocks);
+  int nsplit = min(target / base_blocks, kSplitMaxRanges);
   if (nsplit < 2) nsplit = 1;
   const int n_items = n_kt * nsplit;
   int xcd_per_kv = 0, n_blocks = n_items * a.Hkv;
@@ -392,7 +397,6 @@ hipError_t launch_bwd_dkdv_bf16(const StepArgs& a, const BwdWorkspace& w, hipStr
     xcd_per_kv = 8 / a.Hkv;
     n_blocks = 8 * ((n_items + xcd_per_kv - 1) / xcd_per_kv);
   }
-  const bool no_mask = a.mask == 0 && a.cu == nullptr && a.n_q % kBQ == 0;
   if (no_mask) bwd_dkdv_bf16_kernel<false><<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, w, n_kt, xcd_per_kv, nsplit);
   else bwd_dkdv_bf16_kernel<true><<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, w, n_kt, xcd_per_kv, nsplit);
   hipError_t e = hipGetLastError();

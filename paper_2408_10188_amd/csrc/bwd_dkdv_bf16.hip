@@ -42,7 +42,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   __shared__ __attribute__((aligned(1024))) char stage1[kStage];
   __shared__ __attribute__((aligned(1024))) float stat0[128];      // [0,64) -LSE*log2e, [64,128) delta
   __shared__ __attribute__((aligned(1024))) float stat1[128];
-  __shared__ __attribute__((aligned(1024))) char pxch[2 * 4 * 2048];   // P of a block: [slot][pair][lane * 32 B]
+  __shared__ __attribute__((aligned(1024))) char pxch[2 * 4 * 2048];   // P of a block: [slot][pair][half of the lane's 32 B][lane * 16 B]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, col = lane & 31;
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   for (int ks = 0; ks < 8; ++ks) na[ks] = tile_n_offset(col, ks * 2 + half) + (role_p ? 0 : kTileBytes);            // + qb*8192
 #pragma unroll
   for (int x = 0; x < 4; ++x) ta[x] = tile_t_offset(col, x * 2 + half) + (role_p ? 3 : 2) * kTileBytes;             // + db*4096
-  char* const my_px = pxch + pair * 2048 + lane * 32;    // + slot * 8192
+  char* const my_px = pxch + pair * 2048 + lane * 16;    // + slot * 8192; second 16 bytes of the lane at + 1024
 
   // (head of the group, query tile) of the tile being computed and of the tile whose copies
   // are being issued.  While tile t is computed: the rest of tile t+1 during its first block,
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
         b0 = mk4(pw[0], pw[1], pw[2], pw[3]);
         b1 = mk4(pw[4], pw[5], pw[6], pw[7]);
         *reinterpret_cast<u32x4*>(px) = b0;
-        *reinterpret_cast<u32x4*>(px + 16) = b1;
+        *reinterpret_cast<u32x4*>(px + 1024) = b1;
       } else {
         // dP - delta before the barrier: the statistics belong to the stage being retired
 #pragma unroll
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
       }
       if (!role_p) {
         const u32x4 p0 = *reinterpret_cast<const u32x4*>(px);
-        const u32x4 p1 = *reinterpret_cast<const u32x4*>(px + 16);
+        const u32x4 p1 = *reinterpret_cast<const u32x4*>(px + 1024);
         const uint32_t pw[8] = {p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
         uint32_t sw[8];
 #pragma unroll

@@ -104,8 +104,9 @@ mmsp_status mmsp_zigzag_plan(int64_t T, int32_t N, int32_t rank, int32_t step,
 
 /* Bytes of device workspace the step calls need for blocks of at most n_q_max x n_k_max rows
  * (0 for f32).  The bf16 kernels use it for token-contiguous (transposed) copies of tiles that
- * each call rebuilds before its main kernel; nothing in it outlives a call.  `backward` != 0
- * asks for mmsp_attn_step_bwd.  The workspace must be 16-byte aligned; a call given less
+ * each call rebuilds before its main kernel and, in the backward, for partial dK/dV sums of
+ * key tiles whose query range was cut into several workgroups (a fixed 64 MiB); nothing in it
+ * outlives a call.  `backward` != 0 asks for mmsp_attn_step_bwd.  The workspace must be 16-byte aligned; a call given less
  * returns MMSP_ERR_WORKSPACE_TOO_SMALL.  Two calls that may overlap in time (different
  * streams) need separate workspaces. */
 size_t mmsp_workspace_bytes(const mmsp_shape* shape, int64_t n_q_max, int64_t n_k_max, int backward);

@@ -106,9 +106,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="long", choices=["cfg3", "long", "ulysses"],
+    ap.add_argument("--config", default="long", choices=["cfg3", "long", "ulysses", "2d"],
                     help="long (default, the headline workload) and cfg3: one zigzag rank, fwd+bwd; ulysses: "
-                         "head-shard mode, 7/1 heads over the whole packed 256K sequence, fwd+bwd in one step")
+                         "head-shard mode, 7/1 heads over the whole packed 256K sequence, fwd+bwd in one step; "
+                         "2d: one GPU of a 2D-attention mesh (head degree 4 x ring degree 8): 7/1 heads, zigzag "
+                         "N=8 with 16384-token chunks of the same 256K sequence")
     ap.add_argument("--rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--one-stream", action="store_true", help="all launches on one stream (no overlap of ring steps)")

@@ -102,6 +102,27 @@ mmsp_status mmsp_zigzag_layout(int64_t T, int32_t N, int32_t rank,
 mmsp_status mmsp_zigzag_plan(int64_t T, int32_t N, int32_t rank, int32_t step,
                              int32_t* src_rank, mmsp_block* blk);
 
+/* One GPU's share under 2D-attention -- Sec. 4.2 (the U x R communication mesh) and the
+ * comparison figure's 2D-Attention row: a sequence-parallel group of U * R GPUs computes
+ * attention with the heads split U ways (inside the all-to-all group, which is U consecutive
+ * GPUs) and the sequence split R ways by the zigzag rule (ring group).  GPU g = r * U + u works
+ * on query heads [q_head0, q_head0 + n_q_heads), their KV heads [kv_head0, kv_head0 +
+ * n_kv_heads) (a KV head is replicated on several GPUs when U > n_kv_heads), and runs the R
+ * ring steps of mmsp_zigzag_plan(T, R, ring_rank, step) on chunks chunk_ids[] of length
+ * chunk_len = T / (2R).  Host integers only. */
+typedef struct {
+  int32_t head_rank, ring_rank;      /* u in [0,U), r in [0,R)                              */
+  int32_t q_head0, n_q_heads;
+  int32_t kv_head0, n_kv_heads;
+  int32_t chunk_ids[2];              /* {r, 2R-1-r}                                         */
+  int64_t chunk_len;
+} mmsp_2d_share;
+
+/* INVALID_ARG unless U, R > 0, gpu in [0, U*R), T a positive multiple of 2R, U divides
+ * n_q_heads, n_kv_heads divides n_q_heads, and U divides n_kv_heads or n_kv_heads divides U. */
+mmsp_status mmsp_2d_layout(int64_t T, int32_t U, int32_t R, int32_t gpu, int32_t n_q_heads, int32_t n_kv_heads,
+                           mmsp_2d_share* share);
+
 /* Bytes of device workspace the step calls need for blocks of at most n_q_max x n_k_max rows
  * (0 for f32).  The bf16 kernels use it for token-contiguous (transposed) copies of tiles that
  * each call rebuilds before its main kernel and, in the backward, for partial dK/dV sums of

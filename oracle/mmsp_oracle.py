@@ -173,6 +173,22 @@ def zigzag_layout(T, N, rank):
     return np.array([c0, c1], dtype=np.int32), l2g
 
 
+def two_d_share(T, U, R, gpu, Hq, Hkv):
+    """One GPU's share under 2D-attention (Sec. 4.2, the U x R mesh; the comparison figure's
+    2D-Attention row): the all-to-all group is U consecutive GPUs and splits the heads, the
+    ring group of R splits the sequence by the zigzag rule.  GPU g = r*U + u gets query
+    heads [u*Hq/U, (u+1)*Hq/U), the KV heads those query heads read (head h reads KV head
+    h // (Hq/Hkv)), and the two chunks of ring rank r.
+    Returns dict(u, r, q_heads (array), kv_heads (array), chunk_ids, l2g)."""
+    if not (0 <= gpu < U * R) or Hq % U or Hq % Hkv or (Hkv % U and U % Hkv):
+        raise ValueError("invalid 2D mesh for these heads")
+    u, r = gpu % U, gpu // U
+    q_heads = np.arange(u * (Hq // U), (u + 1) * (Hq // U))
+    kv_heads = np.unique(q_heads // (Hq // Hkv))
+    chunk_ids, l2g = zigzag_layout(T, R, r)
+    return dict(u=u, r=r, q_heads=q_heads, kv_heads=kv_heads, chunk_ids=chunk_ids, l2g=l2g)
+
+
 def zigzag_plan(T, N, rank, step):
     """Which KV block visits rank `rank` at ring step `step`, and which (query rows, key
     rows, mask) sub-block of it holds every visible pair.

@@ -16,7 +16,7 @@ MMSP_OK, MMSP_ERR_INVALID_ARG, MMSP_ERR_UNSUPPORTED, MMSP_ERR_WORKSPACE_TOO_SMAL
 MMSP_MASK_FULL, MMSP_MASK_CAUSAL_DIAG, MMSP_MASK_NONE = 0, 1, 2
 MMSP_BF16, MMSP_F32 = 0, 1
 
-EXPORTS = ["mmsp_zigzag_layout", "mmsp_zigzag_plan", "mmsp_workspace_bytes", "mmsp_attn_step_fwd",
+EXPORTS = ["mmsp_zigzag_layout", "mmsp_zigzag_plan", "mmsp_2d_layout", "mmsp_workspace_bytes", "mmsp_attn_step_fwd",
            "mmsp_attn_merge", "mmsp_attn_delta", "mmsp_attn_step_bwd", "mmsp_last_error"]
 
 
@@ -32,6 +32,12 @@ class MmspBlock(ctypes.Structure):
     _fields_ = [("q_row0", ctypes.c_int64), ("n_q", ctypes.c_int64), ("k_row0", ctypes.c_int64),
                 ("n_k", ctypes.c_int64), ("q_pos0", ctypes.c_int64), ("k_pos0", ctypes.c_int64),
                 ("mask", ctypes.c_int32), ("n_docs", ctypes.c_int32), ("cu_seqlens", ctypes.c_void_p)]
+
+
+class Mmsp2dShare(ctypes.Structure):
+    _fields_ = [("head_rank", ctypes.c_int32), ("ring_rank", ctypes.c_int32), ("q_head0", ctypes.c_int32),
+                ("n_q_heads", ctypes.c_int32), ("kv_head0", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("chunk_ids", ctypes.c_int32 * 2), ("chunk_len", ctypes.c_int64)]
 
 
 class MmspError(RuntimeError):
@@ -50,6 +56,7 @@ _lib.mmsp_last_error.restype = ctypes.c_char_p
 _lib.mmsp_last_error.argtypes = []
 _lib.mmsp_zigzag_layout.argtypes = [_I64, _I32, _I32, ctypes.POINTER(_I32), ctypes.POINTER(_I64)]
 _lib.mmsp_zigzag_plan.argtypes = [_I64, _I32, _I32, _I32, ctypes.POINTER(_I32), ctypes.POINTER(MmspBlock)]
+_lib.mmsp_2d_layout.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, ctypes.POINTER(Mmsp2dShare)]
 _lib.mmsp_workspace_bytes.restype = _SZ
 _lib.mmsp_workspace_bytes.argtypes = [ctypes.POINTER(MmspShape), _I64, _I64, _INT]
 _lib.mmsp_attn_step_fwd.argtypes = [ctypes.POINTER(MmspShape), ctypes.POINTER(MmspBlock), _P, _P, _P, _P, _P, _INT,
@@ -99,6 +106,12 @@ def mmsp_zigzag_plan(T, N, rank, step):
     blk = MmspBlock()
     _check(_lib.mmsp_zigzag_plan(T, N, rank, step, ctypes.byref(src), ctypes.byref(blk)))
     return src.value, blk
+
+
+def mmsp_2d_layout(T, U, R, gpu, n_q_heads, n_kv_heads):
+    share = Mmsp2dShare()
+    _check(_lib.mmsp_2d_layout(T, U, R, gpu, n_q_heads, n_kv_heads, ctypes.byref(share)))
+    return share
 
 
 def mmsp_workspace_bytes(shape, n_q_max, n_k_max, backward):

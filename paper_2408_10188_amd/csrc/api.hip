@@ -137,6 +137,34 @@ mmsp_status mmsp_zigzag_layout(int64_t T, int32_t N, int32_t rank, int32_t chunk
   return MMSP_OK;
 }
 
+mmsp_status mmsp_2d_layout(int64_t T, int32_t U, int32_t R, int32_t gpu, int32_t n_q_heads, int32_t n_kv_heads,
+                           mmsp_2d_share* share) {
+  if (share == nullptr) return fail(MMSP_ERR_INVALID_ARG, "share is NULL");
+  if (U <= 0 || R <= 0) return fail(MMSP_ERR_INVALID_ARG, "U=%d and R=%d must be positive", U, R);
+  if (gpu < 0 || (int64_t)gpu >= (int64_t)U * R) return fail(MMSP_ERR_INVALID_ARG, "gpu=%d is not in [0, U*R=%lld)", gpu, (long long)U * R);
+  if (n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0)
+    return fail(MMSP_ERR_INVALID_ARG, "n_kv_heads=%d must divide n_q_heads=%d", n_kv_heads, n_q_heads);
+  if (n_q_heads % U != 0) return fail(MMSP_ERR_INVALID_ARG, "U=%d must divide n_q_heads=%d", U, n_q_heads);
+  if (n_kv_heads % U != 0 && U % n_kv_heads != 0)
+    return fail(MMSP_ERR_INVALID_ARG, "U=%d must divide n_kv_heads=%d or be a multiple of it", U, n_kv_heads);
+  const int32_t u = gpu % U, r = gpu / U;
+  mmsp_status st = check_zigzag(T, R, r);
+  if (st != MMSP_OK) return st;
+  share->head_rank = u; share->ring_rank = r;
+  share->n_q_heads = n_q_heads / U;
+  share->q_head0 = u * share->n_q_heads;
+  if (n_kv_heads % U == 0) {
+    share->n_kv_heads = n_kv_heads / U;
+    share->kv_head0 = u * share->n_kv_heads;
+  } else {                       // more head ranks than KV heads: U / n_kv_heads GPUs share one KV head
+    share->n_kv_heads = 1;
+    share->kv_head0 = u / (U / n_kv_heads);
+  }
+  share->chunk_ids[0] = r; share->chunk_ids[1] = 2 * R - 1 - r;
+  share->chunk_len = T / (2 * (int64_t)R);
+  return MMSP_OK;
+}
+
 mmsp_status mmsp_zigzag_plan(int64_t T, int32_t N, int32_t rank, int32_t step, int32_t* src_rank, mmsp_block* blk) {
   mmsp_status st = check_zigzag(T, N, rank);
   if (st != MMSP_OK) return st;

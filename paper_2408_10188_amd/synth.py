@@ -65,4 +65,6 @@ CONFIGS = {
     "cfg3":    dict(dtype="bf16", Hq=28, Hkv=4, d=128, N=8,  C=4096, sigma=0.5, seed=0),
     "long":    dict(dtype="bf16", Hq=28, Hkv=4, d=128, N=32, C=4096, sigma=0.5, seed=0),
     "ulysses": dict(dtype="bf16", Hq=7,  Hkv=1, d=128, N=1,  C=131072, sigma=0.5, seed=0),
+    # one GPU of a 2D-attention mesh, head degree 4 x ring degree 8 over the 28/4-head, 256K-token workload
+    "2d":      dict(dtype="bf16", Hq=7,  Hkv=1, d=128, N=8,  C=16384, sigma=0.5, seed=0),
 }

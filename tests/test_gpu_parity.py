@@ -258,3 +258,50 @@ def test_strided_q_and_kv_views():
         torch.cuda.synchronize()
         outs.append((o, lse))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
+@pytest.mark.parametrize("U,R,Hq,Hkv", [(2, 2, 4, 2), (4, 2, 4, 2)])
+def test_two_d_attention_shares(U, R, Hq, Hkv):
+    """2D-attention: every GPU of a U x R mesh runs the ring steps of its ring rank on its own
+    heads (strided head slices of the full tensors); together they must give the unsharded
+    causal result of the oracle.  The second case has more head ranks than KV heads."""
+    C, d = 96, 128
+    cfg = dict(dtype="bf16", Hq=Hq, Hkv=Hkv, d=d, N=R, C=C, sigma=0.5, seed=17)
+    prob = RankProblem(cfg)
+    T, n = prob.T, 2 * C
+    K64, V64 = prob.K_full().astype(np.float64), prob.V_full().astype(np.float64)
+    dK_sum = np.zeros((T, Hkv, d)); dV_sum = np.zeros((T, Hkv, d))
+    ref_by_rank = {}
+    for g in range(U * R):
+        sh = B.mmsp_2d_layout(T, U, R, g, Hq, Hkv)
+        r, h0, nh, kv0, nkv = sh.ring_rank, sh.q_head0, sh.n_q_heads, sh.kv_head0, sh.n_kv_heads
+        q, do = prob.rank_inputs(r)
+        if r not in ref_by_rank:
+            _, l2g = orc.zigzag_layout(T, R, r)
+            ref_by_rank[r] = (l2g, orc.causal_attention(q.astype(np.float64), K64, V64, prob.scale, q_pos=l2g,
+                                                        dO=do.astype(np.float64)))
+        l2g, ref = ref_by_rank[r]
+        qd = to_dev(q, True)[:, h0:h0 + nh]                         # strided views: heads of this GPU only
+        k_zz, v_zz = prob.k_zz[:, :, kv0:kv0 + nkv], prob.v_zz[:, :, kv0:kv0 + nkv]
+        dod = to_dev(do, True)[:, h0:h0 + nh].contiguous()
+        shape = ring.shape_for(qd, k_zz, B.MMSP_BF16, n, prob.scale)
+        o_acc = torch.empty(n, nh, d, dtype=torch.float32, device=DEV)
+        lse = torch.empty(nh, n, dtype=torch.float32, device=DEV)
+        o_final = torch.empty(n, nh, d, dtype=torch.bfloat16, device=DEV)
+        delta, dq = torch.empty_like(lse), torch.zeros_like(o_acc)
+        dk = torch.zeros(R, n, nkv, d, dtype=torch.float32, device=DEV)
+        dv = torch.zeros_like(dk)
+        ws_bytes = ring.workspace_bytes(shape, n, n)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+        ring.rank_forward(shape, T, R, r, qd, k_zz, v_zz, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes)
+        ring.rank_backward(shape, T, R, r, qd, k_zz, v_zz, o_final, dod, lse, delta, dq, dk, dv, ws=ws, ws_bytes=ws_bytes)
+        torch.cuda.synchronize()
+        errs = dict(o=max_abs(to_host64(o_acc), ref[0][:, h0:h0 + nh]), lse=max_abs(to_host64(lse), ref[1][h0:h0 + nh]),
+                    dq=max_abs(to_host64(dq), ref[2][:, h0:h0 + nh]))
+        assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 and errs["dq"] <= 2e-2, (g, errs)
+        dK_sum[:, kv0:kv0 + nkv] += prob.unzigzag(to_host64(dk))
+        dV_sum[:, kv0:kv0 + nkv] += prob.unzigzag(to_host64(dv))
+    # dK / dV: sum over every GPU (ring ranks, and head ranks that share a KV head) = unsharded gradient
+    dK_ref = sum(ref_by_rank[r][1][3] for r in range(R))
+    dV_ref = sum(ref_by_rank[r][1][4] for r in range(R))
+    assert max_abs(dK_sum, dK_ref) <= 2e-2 and max_abs(dV_sum, dV_ref) <= 2e-2

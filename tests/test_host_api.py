@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "mmsp.h")).read()
-    declared = set(re.findall(r"\b(mmsp_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(mmsp_[a-z0-9_]+)\s*\(", header))
     assert declared == set(B.EXPORTS)
     for name in declared:
         assert hasattr(B._lib, name), name
@@ -40,6 +40,25 @@ def test_layout_and_plan_match_the_oracle_bit_for_bit(T, N):
 def test_layout_of_the_papers_example():
     got = [B.mmsp_zigzag_layout(8, 4, r)[1].tolist() for r in range(4)]
     assert got == [[0, 7], [1, 6], [2, 5], [3, 4]]
+
+
+@pytest.mark.parametrize("T,U,R,Hq,Hkv", [(8, 2, 2, 2, 2), (48, 4, 2, 8, 2), (262144, 4, 8, 28, 4), (24, 8, 1, 8, 2), (64, 1, 4, 6, 3)])
+def test_two_d_layout_matches_the_oracle_bit_for_bit(T, U, R, Hq, Hkv):
+    for g in range(U * R):
+        sh = B.mmsp_2d_layout(T, U, R, g, Hq, Hkv)
+        ref = orc.two_d_share(T, U, R, g, Hq, Hkv)
+        assert (sh.head_rank, sh.ring_rank) == (ref["u"], ref["r"])
+        assert list(range(sh.q_head0, sh.q_head0 + sh.n_q_heads)) == ref["q_heads"].tolist()
+        assert list(range(sh.kv_head0, sh.kv_head0 + sh.n_kv_heads)) == ref["kv_heads"].tolist()
+        assert list(sh.chunk_ids) == ref["chunk_ids"].tolist() and sh.chunk_len == T // (2 * R)
+
+
+@pytest.mark.parametrize("args", [(8, 0, 2, 0, 2, 2), (8, 2, 2, 4, 2, 2), (8, 2, 2, -1, 2, 2), (10, 2, 2, 0, 2, 2),
+                                  (8, 3, 2, 0, 4, 2), (8, 2, 2, 0, 6, 4), (24, 4, 1, 0, 12, 6)])
+def test_two_d_layout_rejects_bad_arguments(args):
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_2d_layout(*args)
+    assert e.value.status == B.MMSP_ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("T,N,rank", [(10, 4, 0), (8, 0, 0), (8, 4, 4), (8, 4, -1), (0, 1, 0), (-8, 4, 0)])

@@ -244,6 +244,52 @@ def test_plain_ring_imbalance_example():
         assert busy == int(rounds)
 
 
+# ---------------------------------------------------------------- 2D-attention shares
+def test_two_d_share_matches_the_papers_example():
+    for g, r, u, head, t0, t1, t2, t3, pairs in _read_rows("two_d_8_2x2.txt"):
+        sh = orc.two_d_share(8, 2, 2, int(g), 2, 2)
+        assert (sh["r"], sh["u"]) == (int(r), int(u))
+        assert sh["q_heads"].tolist() == [int(head)] and sh["kv_heads"].tolist() == [int(head)]
+        assert sh["l2g"].tolist() == [int(t0), int(t1), int(t2), int(t3)]
+        assert orc.causal_pairs_of_rank(8, 2, sh["r"]) == int(pairs)
+
+
+@pytest.mark.parametrize("T,U,R,Hq,Hkv", [(8, 2, 2, 2, 2), (48, 4, 2, 8, 2), (64, 2, 4, 4, 4), (262144, 4, 8, 28, 4), (24, 8, 1, 8, 2)])
+def test_two_d_shares_partition_heads_and_tokens(T, U, R, Hq, Hkv):
+    """Every (query head, token) belongs to exactly one GPU; a GPU holds the KV heads its query
+    heads read and no others; GPUs of one all-to-all group share their tokens."""
+    seen = np.zeros((Hq, T), dtype=np.int32)
+    for g in range(U * R):
+        sh = orc.two_d_share(T, U, R, g, Hq, Hkv)
+        seen[np.ix_(sh["q_heads"], sh["l2g"])] += 1
+        assert set(sh["kv_heads"].tolist()) == {h // (Hq // Hkv) for h in sh["q_heads"].tolist()}
+        assert len(sh["q_heads"]) == Hq // U and len(sh["l2g"]) == T // R
+        assert np.array_equal(sh["l2g"], orc.two_d_share(T, U, R, (g // U) * U, Hq, Hkv)["l2g"])
+    assert np.all(seen == 1)
+
+
+def test_two_d_sharded_attention_reassembles_the_unsharded_result():
+    """Each GPU runs the ring emulation of its ring rank on its own heads only; together they
+    give the unsharded O, LSE, dQ and (summed over ring ranks) dK, dV."""
+    rng = np.random.default_rng(21)
+    U, R, C, Hq, Hkv, d = 2, 2, 3, 4, 2, 5
+    T = 2 * R * C
+    Q, K, V, dO = _rand(rng, T, Hq, d), _rand(rng, T, Hkv, d), _rand(rng, T, Hkv, d), _rand(rng, T, Hq, d)
+    scale = 1 / math.sqrt(d)
+    O_ref, L_ref, dQ_ref, dK_ref, dV_ref = orc.causal_attention(Q, K, V, scale, dO=dO)
+    O = np.zeros_like(O_ref); L = np.zeros_like(L_ref); dQ = np.zeros_like(Q)
+    dK = np.zeros_like(K); dV = np.zeros_like(V)
+    for g in range(U * R):
+        sh = orc.two_d_share(T, U, R, g, Hq, Hkv)
+        qh, kh, l2g, r = sh["q_heads"], sh["kv_heads"], sh["l2g"], sh["r"]
+        o, l = orc.ring_rank_fwd(Q[:, qh], K[:, kh], V[:, kh], R, r, scale)
+        dq, dk, dv = orc.ring_rank_bwd(Q[:, qh], K[:, kh], V[:, kh], dO[np.ix_(l2g, qh)], o, l, R, r, scale)
+        O[np.ix_(l2g, qh)] = o; L[np.ix_(qh, l2g)] = l; dQ[np.ix_(l2g, qh)] = dq
+        dK[:, kh] += dk; dV[:, kh] += dv
+    for got, ref in [(O, O_ref), (L, L_ref), (dQ, dQ_ref), (dK, dK_ref), (dV, dV_ref)]:
+        np.testing.assert_allclose(got, ref, atol=1e-12)
+
+
 # ---------------------------------------------------------------- ring emulation
 @pytest.mark.parametrize("N,C,Hq,Hkv", [(2, 4, 2, 1), (3, 5, 6, 2), (4, 3, 4, 4)])
 def test_ring_emulation_reassembles_the_unsharded_result(N, C, Hq, Hkv):

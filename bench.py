@@ -101,6 +101,51 @@ def bench_ulysses(args, cfg, torch, np, B, ring, synth):
     }
 
 
+def bench_packed(args, cfg, torch, np, B, ring, synth, env):
+    """One zigzag rank over a packed sequence: document-causal mask on global positions."""
+    N, C, Hq, Hkv, d, T, rank = (env[k] for k in ("N", "C", "Hq", "Hkv", "d", "T", "rank"))
+    q, d_o, k_zz, v_zz, shape, ws, ws_bytes = (env[k] for k in ("q", "d_o", "k_zz", "v_zz", "shape", "ws", "ws_bytes"))
+    o_acc, lse, o_final, delta, dq, dk_zz, dv_zz = (env[k] for k in ("o_acc", "lse", "o_final", "delta", "dq", "dk_zz", "dv_zz"))
+    cu = synth.packed_cu_seqlens(T, cfg["seed"])
+    cud = torch.from_numpy(cu).to("cuda:0")
+    n_docs = len(cu) - 1
+
+    def one_pass():
+        ring.rank_forward_packed(shape, T, N, rank, q, k_zz, v_zz, cud, n_docs, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes,
+                                 cu_host=cu)
+        dq.zero_()
+        ring.rank_backward_packed(shape, T, N, rank, q, k_zz, v_zz, cud, n_docs, o_final, d_o, lse, delta, dq, dk_zz, dv_zz,
+                                  ws=ws, ws_bytes=ws_bytes, cu_host=cu)
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_pass()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+    # visible pairs of this rank's rows: position - start of its document + 1
+    pos = np.concatenate([np.arange(c * C, (c + 1) * C, dtype=np.int64) for c in (rank, 2 * N - 1 - rank)])
+    start = cu[np.searchsorted(cu, pos, side="right") - 1].astype(np.int64)
+    pairs = int((pos - start + 1).sum())
+    all_pos = np.arange(T, dtype=np.int64)
+    total = int((all_pos - cu[np.searchsorted(cu, all_pos, side="right") - 1] + 1).sum())
+    value = 14 * d * Hq * pairs / (ms_per_step * 1e-3) / 1e12
+    return {
+        "metric": "causal attention TFLOP/s fwd+bwd per rank shard; % of MI355X bf16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic", "frac_of_bf16_dense_peak": value / BF16_DENSE_PEAK_TFLOPS,
+        "config": {"workload": "%s packed: zigzag rank %d of N=%d, C=%d (T=%d) over %d packed documents, %d/%d heads, d=%d, "
+                               "bf16, fwd+bwd, document-causal mask" % (args.config, rank, N, C, T, n_docs, Hq, Hkv, d),
+                   "streams": 1, "pairs_per_head": pairs, "share_of_all_pairs": pairs / total, "balanced_share": 1.0 / N},
+        "roofline": {"kernel": "fwd+bwd (all kernels of the pass)", "bound": "mfma", "achieved": value,
+                     "peak": BF16_DENSE_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": value / BF16_DENSE_PEAK_TFLOPS, "traffic": None},
+        "cpu_baseline": None,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -113,6 +158,9 @@ def main():
                          "N=8 with 16384-token chunks of the same 256K sequence")
     ap.add_argument("--rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--packed", action="store_true",
+                    help="zigzag workloads: the sequence is packed from documents (synth.packed_cu_seqlens) and the ring "
+                         "steps run the sub-blocks of mmsp_zigzag_plan_packed under the document-causal mask, one stream")
     ap.add_argument("--one-stream", action="store_true", help="all launches on one stream (no overlap of ring steps)")
     ap.add_argument("--cpu-rows", type=int, default=32, help="query rows per chunk in the oracle sample")
     ap.add_argument("--ceiling", action="store_true",
@@ -197,6 +245,10 @@ def main():
         dq.zero_()
         ring.rank_backward(shape, T, N, rank, q, k_zz, v_zz, o_final, d_o, lse, delta, dq, dk_zz, dv_zz, ws=ws,
                            ws_bytes=ws_bytes, side=side)
+
+    if args.packed:
+        print(json.dumps(bench_packed(args, cfg, torch, np, B, ring, synth, locals())))
+        return
 
     for _ in range(args.warmup):
         one_pass()

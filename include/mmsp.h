@@ -102,6 +102,25 @@ mmsp_status mmsp_zigzag_layout(int64_t T, int32_t N, int32_t rank,
 mmsp_status mmsp_zigzag_plan(int64_t T, int32_t N, int32_t rank, int32_t step,
                              int32_t* src_rank, mmsp_block* blk);
 
+/* The same ring step for a packed (variable-length) sequence whose document mask is given by
+ * cu_seqlens on global positions -- Sec. 4.2 "MM-SP workflow" (token-level sharding of the
+ * packed vision + text inputs from both ends).  A rank's local rows are two segments with
+ * different global positions, and so is the visiting block, so the step is cut into
+ * sub-blocks of one query segment x one key segment, inside which positions are consecutive:
+ * blks[0 .. *n_blocks) (at most 4, 3 for the own block, 2 otherwise) are MMSP_MASK_CAUSAL_DIAG
+ * blocks of C x C rows with q_pos0 / k_pos0 set to global positions; segment pairs in which no
+ * key can precede a query are left out, and so are, when the host copy cu_seqlens_host
+ * ([n_docs + 1], may be NULL) is given, segment pairs that no document spans (*n_blocks can
+ * then be 0).  The blocks' cu_seqlens / n_docs are left NULL / 0 for the caller to fill in with
+ * the device copy (with NULL the sub-blocks reproduce the plain causal plan).  The forward
+ * calls accumulate in order; in the backward a key segment touched by two sub-blocks of a step
+ * needs accumulate_dkdv on the second, and key rows of the visiting block that no sub-block
+ * touches receive no gradient from this step.  Errors as mmsp_zigzag_plan, and INVALID_ARG if
+ * cu_seqlens_host is given with n_docs <= 0. */
+mmsp_status mmsp_zigzag_plan_packed(int64_t T, int32_t N, int32_t rank, int32_t step,
+                                    const int32_t* cu_seqlens_host, int32_t n_docs,
+                                    int32_t* src_rank, mmsp_block blks[4], int32_t* n_blocks);
+
 /* One GPU's share under 2D-attention -- Sec. 4.2 (the U x R communication mesh) and the
  * comparison figure's 2D-Attention row: a sequence-parallel group of U * R GPUs computes
  * attention with the heads split U ways (inside the all-to-all group, which is U consecutive

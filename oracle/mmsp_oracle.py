@@ -209,6 +209,31 @@ def zigzag_plan(T, N, rank, step):
     return dict(src=src, q_row0=C, n_q=C, k_row0=0, n_k=2 * C, q_pos0=0, k_pos0=0, mask=MASK_FULL)
 
 
+def zigzag_plan_packed(T, N, rank, step, cu_seqlens=None):
+    """Ring step `step` of rank `rank` for a packed sequence (document mask from cu_seqlens on
+    global positions): the local rows are two segments with positions chunk_r*C.. and
+    chunk_(2N-1-r)*C.., the visiting block likewise, so the step is cut into sub-blocks of one
+    query segment x one key segment, inside which positions are consecutive.  A (query chunk a,
+    key chunk b) pair holds visible pairs only if b <= a; it is emitted as a causal-diagonal
+    block on global positions (for b < a every pair passes the causal test and only the
+    document test remains).  With cu_seqlens, segment pairs without any same-document
+    (query, key) pair are left out.  Returns (src, [blk, ...])."""
+    C = T // (2 * N)
+    src = (rank - step) % N
+    q_chunks = (rank, 2 * N - 1 - rank)
+    k_chunks = (src, 2 * N - 1 - src)
+    blks = []
+    for qi, a in enumerate(q_chunks):
+        for ki, b in enumerate(k_chunks):
+            if b <= a:
+                if cu_seqlens is not None and b < a and not np.any(
+                        visible(np.arange(a * C, (a + 1) * C), np.arange(b * C, (b + 1) * C), cu_seqlens)):
+                    continue
+                blks.append(dict(src=src, q_row0=qi * C, n_q=C, k_row0=ki * C, n_k=C, q_pos0=a * C, k_pos0=b * C,
+                                 mask=MASK_CAUSAL_DIAG))
+    return src, blks
+
+
 def causal_pairs_of_rank(T, N, rank):
     """Exact number of visible (query, key) pairs for one query head of one rank."""
     _, l2g = zigzag_layout(T, N, rank)
@@ -311,4 +336,40 @@ def ring_rank_bwd(Q, K, V, dO_local, O_local, LSE_local, N, rank, scale):
         rows = src_rows[blk["k_row0"]: blk["k_row0"] + blk["n_k"]]
         dK[rows] += dk
         dV[rows] += dv
+    return dQ, dK, dV
+
+
+def ring_rank_fwd_packed(Q, K, V, N, rank, scale, cu_seqlens):
+    """ring_rank_fwd for a packed sequence: the sub-blocks of zigzag_plan_packed, merged."""
+    T = Q.shape[0]
+    _, l2g = zigzag_layout(T, N, rank)
+    Ql = Q[l2g]
+    O = np.zeros((len(l2g), Q.shape[1], V.shape[2]))
+    L = np.full((Q.shape[1], len(l2g)), NEG_INF)
+    for s in range(N):
+        src, blks = zigzag_plan_packed(T, N, rank, s)
+        _, src_rows = zigzag_layout(T, N, src)
+        for blk in blks:
+            O_p, L_p = step_fwd(Ql, K[src_rows], V[src_rows], blk, scale, cu_seqlens)
+            r0, r1 = blk["q_row0"], blk["q_row0"] + blk["n_q"]
+            O[r0:r1], L[:, r0:r1] = merge(O[r0:r1], L[:, r0:r1], O_p, L_p)
+    return O, L
+
+
+def ring_rank_bwd_packed(Q, K, V, dO_local, O_local, LSE_local, N, rank, scale, cu_seqlens):
+    """ring_rank_bwd for a packed sequence."""
+    T = Q.shape[0]
+    _, l2g = zigzag_layout(T, N, rank)
+    Ql = Q[l2g]
+    D = delta(dO_local, O_local)
+    dQ, dK, dV = np.zeros_like(Ql), np.zeros_like(K), np.zeros_like(V)
+    for s in range(N):
+        src, blks = zigzag_plan_packed(T, N, rank, s)
+        _, src_rows = zigzag_layout(T, N, src)
+        for blk in blks:
+            dq, dk, dv = step_bwd(Ql, K[src_rows], V[src_rows], dO_local, LSE_local, D, blk, scale, cu_seqlens)
+            dQ[blk["q_row0"]: blk["q_row0"] + blk["n_q"]] += dq
+            rows = src_rows[blk["k_row0"]: blk["k_row0"] + blk["n_k"]]
+            dK[rows] += dk
+            dV[rows] += dv
     return dQ, dK, dV

@@ -16,7 +16,7 @@ MMSP_OK, MMSP_ERR_INVALID_ARG, MMSP_ERR_UNSUPPORTED, MMSP_ERR_WORKSPACE_TOO_SMAL
 MMSP_MASK_FULL, MMSP_MASK_CAUSAL_DIAG, MMSP_MASK_NONE = 0, 1, 2
 MMSP_BF16, MMSP_F32 = 0, 1
 
-EXPORTS = ["mmsp_zigzag_layout", "mmsp_zigzag_plan", "mmsp_2d_layout", "mmsp_workspace_bytes", "mmsp_attn_step_fwd",
+EXPORTS = ["mmsp_zigzag_layout", "mmsp_zigzag_plan", "mmsp_zigzag_plan_packed", "mmsp_2d_layout", "mmsp_workspace_bytes", "mmsp_attn_step_fwd",
            "mmsp_attn_merge", "mmsp_attn_delta", "mmsp_attn_step_bwd", "mmsp_last_error"]
 
 
@@ -56,6 +56,8 @@ _lib.mmsp_last_error.restype = ctypes.c_char_p
 _lib.mmsp_last_error.argtypes = []
 _lib.mmsp_zigzag_layout.argtypes = [_I64, _I32, _I32, ctypes.POINTER(_I32), ctypes.POINTER(_I64)]
 _lib.mmsp_zigzag_plan.argtypes = [_I64, _I32, _I32, _I32, ctypes.POINTER(_I32), ctypes.POINTER(MmspBlock)]
+_lib.mmsp_zigzag_plan_packed.argtypes = [_I64, _I32, _I32, _I32, ctypes.POINTER(_I32), _I32, ctypes.POINTER(_I32),
+                                         ctypes.POINTER(MmspBlock), ctypes.POINTER(_I32)]
 _lib.mmsp_2d_layout.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, ctypes.POINTER(Mmsp2dShare)]
 _lib.mmsp_workspace_bytes.restype = _SZ
 _lib.mmsp_workspace_bytes.argtypes = [ctypes.POINTER(MmspShape), _I64, _I64, _INT]
@@ -106,6 +108,24 @@ def mmsp_zigzag_plan(T, N, rank, step):
     blk = MmspBlock()
     _check(_lib.mmsp_zigzag_plan(T, N, rank, step, ctypes.byref(src), ctypes.byref(blk)))
     return src.value, blk
+
+
+def mmsp_zigzag_plan_packed(T, N, rank, step, cu_seqlens=None, n_docs=0, cu_host=None):
+    """Returns (src, [blocks]); cu_seqlens (device int32 tensor) / n_docs are filled into every
+    block; cu_host (numpy int32 copy of cu_seqlens) lets the plan drop segment pairs no document spans."""
+    src, n = _I32(), _I32()
+    blks = (MmspBlock * 4)()
+    hp, hn = None, 0
+    if cu_host is not None:
+        cu_host = np.ascontiguousarray(cu_host, dtype=np.int32)
+        hp, hn = cu_host.ctypes.data_as(ctypes.POINTER(_I32)), len(cu_host) - 1
+    _check(_lib.mmsp_zigzag_plan_packed(T, N, rank, step, hp, hn, ctypes.byref(src), blks, ctypes.byref(n)))
+    out = []
+    for i in range(n.value):
+        b = MmspBlock.from_buffer_copy(blks[i])
+        b.cu_seqlens, b.n_docs = _ptr(cu_seqlens), n_docs
+        out.append(b)
+    return src.value, out
 
 
 def mmsp_2d_layout(T, U, R, gpu, n_q_heads, n_kv_heads):

@@ -137,6 +137,42 @@ mmsp_status mmsp_zigzag_layout(int64_t T, int32_t N, int32_t rank, int32_t chunk
   return MMSP_OK;
 }
 
+mmsp_status mmsp_zigzag_plan_packed(int64_t T, int32_t N, int32_t rank, int32_t step, const int32_t* cu_seqlens_host,
+                                    int32_t n_docs, int32_t* src_rank, mmsp_block blks[4], int32_t* n_blocks) {
+  mmsp_status st = check_zigzag(T, N, rank);
+  if (st != MMSP_OK) return st;
+  if (step < 0 || step >= N) return fail(MMSP_ERR_INVALID_ARG, "step=%d is not in [0, %d)", step, N);
+  if (src_rank == nullptr || blks == nullptr || n_blocks == nullptr)
+    return fail(MMSP_ERR_INVALID_ARG, "src_rank, blks or n_blocks is NULL");
+  if (cu_seqlens_host != nullptr && n_docs <= 0) return fail(MMSP_ERR_INVALID_ARG, "cu_seqlens_host given with n_docs=%d", n_docs);
+  const int64_t C = T / (2 * (int64_t)N);
+  const int32_t src = ((rank - step) % N + N) % N;
+  *src_rank = src;
+  const int32_t q_chunk[2] = {rank, 2 * N - 1 - rank}, k_chunk[2] = {src, 2 * N - 1 - src};
+  int32_t n = 0;
+  for (int qi = 0; qi < 2; ++qi)
+    for (int ki = 0; ki < 2; ++ki) {
+      if (k_chunk[ki] > q_chunk[qi]) continue;          // every key of the segment follows every query
+      if (cu_seqlens_host != nullptr && k_chunk[ki] < q_chunk[qi]) {
+        // A document is contiguous: one that holds a key of the earlier chunk and a query of the
+        // later chunk holds the later chunk's first position, so it must start before the
+        // earlier chunk ends.  Positions outside every document see nothing.
+        const int64_t p = q_chunk[qi] * C;
+        if (p >= cu_seqlens_host[n_docs] || p < cu_seqlens_host[0]) continue;
+        int32_t lo = 0, hi = n_docs;                    // cu[lo] <= p < cu[hi]
+        while (hi - lo > 1) { const int32_t m = (lo + hi) / 2; if (cu_seqlens_host[m] <= p) lo = m; else hi = m; }
+        if (cu_seqlens_host[lo] >= (k_chunk[ki] + 1) * C) continue;
+      }
+      mmsp_block* b = &blks[n++];
+      memset(b, 0, sizeof(*b));
+      b->q_row0 = qi * C; b->n_q = C; b->k_row0 = ki * C; b->n_k = C;
+      b->q_pos0 = q_chunk[qi] * C; b->k_pos0 = k_chunk[ki] * C;
+      b->mask = MMSP_MASK_CAUSAL_DIAG;
+    }
+  *n_blocks = n;
+  return MMSP_OK;
+}
+
 mmsp_status mmsp_2d_layout(int64_t T, int32_t U, int32_t R, int32_t gpu, int32_t n_q_heads, int32_t n_kv_heads,
                            mmsp_2d_share* share) {
   if (share == nullptr) return fail(MMSP_ERR_INVALID_ARG, "share is NULL");

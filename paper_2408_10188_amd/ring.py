@@ -114,6 +114,37 @@ def rank_backward(shape, T, N, rank, q, k_zz, v_zz, o_final, d_o, lse, delta, dq
                              dk_zz[src], dv_zz[src], False, ws, ws_bytes, stream)
 
 
+def rank_forward_packed(shape, T, N, rank, q, k_zz, v_zz, cu_seqlens, n_docs, o_acc, lse, o_final=None, stream=0,
+                        ws=None, ws_bytes=0, cu_host=None):
+    """Zigzag ring steps of `rank` over a packed sequence (document-causal mask from cu_seqlens
+    on global positions): the sub-blocks of mmsp_zigzag_plan_packed, merged in the step epilogue.
+    cu_host (host copy of cu_seqlens) lets the plan skip segment pairs that no document spans."""
+    n_rows = q.shape[0]
+    B.mmsp_attn_step_fwd(shape, B.make_block(0, n_rows, 0, 0, B.MMSP_MASK_NONE, 0, 0), q, k_zz[0], v_zz[0], o_acc, lse,
+                         False, ws, ws_bytes, stream)          # rows whose document lies in no visited segment stay empty
+    for s in range(N):
+        src, blks = B.mmsp_zigzag_plan_packed(T, N, rank, s, cu_seqlens, n_docs, cu_host)
+        for blk in blks:
+            B.mmsp_attn_step_fwd(shape, blk, q, k_zz[src], v_zz[src], o_acc, lse, True, ws, ws_bytes, stream)
+    if o_final is not None:
+        B.mmsp_attn_merge(shape, 0, n_rows, o_acc, lse, None, None, o_final, stream=stream)
+
+
+def rank_backward_packed(shape, T, N, rank, q, k_zz, v_zz, cu_seqlens, n_docs, o_final, d_o, lse, delta, dq, dk_zz,
+                         dv_zz, stream=0, ws=None, ws_bytes=0, cu_host=None):
+    """Backward of rank_forward_packed.  dq must be zero on entry; the key rows a step reaches
+    are overwritten by its first sub-block and accumulated into by the next one."""
+    n_rows = q.shape[0]
+    B.mmsp_attn_delta(shape, 0, n_rows, o_final, d_o, delta, stream=stream)
+    for s in range(N):
+        src, blks = B.mmsp_zigzag_plan_packed(T, N, rank, s, cu_seqlens, n_docs, cu_host)
+        seen = set()
+        for blk in blks:
+            B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, False, dq,
+                                 dk_zz[src], dv_zz[src], blk.k_row0 in seen, ws, ws_bytes, stream)
+            seen.add(blk.k_row0)
+
+
 def ulysses_forward(shape, T, q, k, v, cu_seqlens, n_docs, o_acc, lse, o_final=None, stream=0, ws=None, ws_bytes=0):
     """Head-shard mode: the whole packed sequence in one step under the document-causal mask."""
     blk = B.make_block(0, T, 0, T, B.MMSP_MASK_CAUSAL_DIAG, 0, 0, cu_seqlens, n_docs)

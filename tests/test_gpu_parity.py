@@ -305,3 +305,46 @@ def test_two_d_attention_shares(U, R, Hq, Hkv):
     dK_ref = sum(ref_by_rank[r][1][3] for r in range(R))
     dV_ref = sum(ref_by_rank[r][1][4] for r in range(R))
     assert max_abs(dK_sum, dK_ref) <= 2e-2 and max_abs(dV_sum, dV_ref) <= 2e-2
+
+
+@pytest.mark.parametrize("dtype,N,C,d,cuts", [("bf16", 3, 96, 128, (1, 70, 96, 200, 333, 500)), ("bf16", 2, 160, 128, (320,)),
+                                            ("f32", 2, 64, 64, (5, 130, 131))])
+def test_zigzag_ring_over_packed_documents(dtype, N, C, d, cuts):
+    """Zigzag ring steps with a document mask on global positions (sub-blocks of
+    mmsp_zigzag_plan_packed): documents that start and end inside chunks, one that spans a
+    chunk boundary, one that exactly fills the first rank's first chunk."""
+    cfg = dict(dtype=dtype, Hq=4, Hkv=2, d=d, N=N, C=C, sigma=0.5, seed=23)
+    prob = RankProblem(cfg)
+    bf16 = dtype == "bf16"
+    tol = TOL_BF16 if bf16 else TOL_F32
+    T, n = prob.T, 2 * C
+    cu = np.array([0, *cuts, T], dtype=np.int32)
+    cud = torch.from_numpy(cu).to(DEV)
+    K64, V64 = prob.K_full().astype(np.float64), prob.V_full().astype(np.float64)
+    dK_sum = np.zeros_like(K64); dV_sum = np.zeros_like(V64)
+    dK_ref = np.zeros_like(K64); dV_ref = np.zeros_like(V64)
+    for r in range(N):
+        q, do = prob.rank_inputs(r)
+        _, l2g = orc.zigzag_layout(T, N, r)
+        ref = orc.causal_attention(q.astype(np.float64), K64, V64, prob.scale, cu_seqlens=cu, q_pos=l2g, dO=do.astype(np.float64))
+        qd, dod = to_dev(q, bf16), to_dev(do, bf16)
+        shape = ring.shape_for(qd, prob.k_zz, B.MMSP_BF16 if bf16 else B.MMSP_F32, n, prob.scale)
+        o_acc = torch.empty(n, prob.Hq, d, dtype=torch.float32, device=DEV)
+        lse = torch.empty(prob.Hq, n, dtype=torch.float32, device=DEV)
+        o_final = torch.empty_like(qd)
+        delta, dq = torch.empty_like(lse), torch.zeros_like(o_acc)
+        dk = torch.zeros(N, n, prob.Hkv, d, dtype=torch.float32, device=DEV)
+        dv = torch.zeros_like(dk)
+        ws_bytes = ring.workspace_bytes(shape, n, n)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=DEV)
+        cu_host = cu if r % 2 == 0 else None               # with and without the host-side pruning of empty segment pairs
+        ring.rank_forward_packed(shape, T, N, r, qd, prob.k_zz, prob.v_zz, cud, len(cu) - 1, o_acc, lse, o_final, ws=ws,
+                                 ws_bytes=ws_bytes, cu_host=cu_host)
+        ring.rank_backward_packed(shape, T, N, r, qd, prob.k_zz, prob.v_zz, cud, len(cu) - 1, o_final, dod, lse, delta, dq,
+                                  dk, dv, ws=ws, ws_bytes=ws_bytes, cu_host=cu_host)
+        torch.cuda.synchronize()
+        errs = dict(o=max_abs(to_host64(o_acc), ref[0]), lse=max_abs(to_host64(lse), ref[1]), dq=max_abs(to_host64(dq), ref[2]))
+        assert errs["o"] <= tol["o"] and errs["lse"] <= tol["lse"] and errs["dq"] <= tol["g"], (r, errs)
+        dK_sum += prob.unzigzag(to_host64(dk)); dV_sum += prob.unzigzag(to_host64(dv))
+        dK_ref += ref[3]; dV_ref += ref[4]
+    assert max_abs(dK_sum, dK_ref) <= tol["g"] and max_abs(dV_sum, dV_ref) <= tol["g"]

@@ -37,6 +37,40 @@ def test_layout_and_plan_match_the_oracle_bit_for_bit(T, N):
             assert blk.cu_seqlens is None and blk.n_docs == 0
 
 
+@pytest.mark.parametrize("T,N", [(8, 4), (96, 3), (65536, 8), (262144, 32)])
+def test_packed_plan_matches_the_oracle_bit_for_bit(T, N):
+    for r in range(N):
+        for s in range(N):
+            src, blks = B.mmsp_zigzag_plan_packed(T, N, r, s)
+            src_o, blks_o = orc.zigzag_plan_packed(T, N, r, s)
+            assert src == src_o and len(blks) == len(blks_o)
+            for blk, ref in zip(blks, blks_o):
+                got = dict(src=src, q_row0=blk.q_row0, n_q=blk.n_q, k_row0=blk.k_row0, n_k=blk.n_k,
+                           q_pos0=blk.q_pos0, k_pos0=blk.k_pos0, mask=blk.mask)
+                assert got == ref and blk.cu_seqlens is None and blk.n_docs == 0
+    with pytest.raises(B.MmspError):
+        B.mmsp_zigzag_plan_packed(T, N, 0, N)
+
+
+@pytest.mark.parametrize("T,N,cu", [(48, 3, [0, 5, 8, 9, 30, 48]), (64, 4, [0, 64]), (64, 4, [0, 8, 16, 24, 32, 40, 48, 56, 64]),
+                                    (64, 2, [3, 20, 50]), (96, 3, [0, 16, 17, 33, 80, 96])])
+def test_packed_plan_pruning_matches_the_oracle(T, N, cu):
+    """With the host copy of cu_seqlens the plan drops exactly the segment pairs in which the
+    oracle's visibility matrix is empty (documents aligned with chunks, spanning several, or
+    leaving positions outside every document)."""
+    cu = np.asarray(cu, dtype=np.int32)
+    dropped = 0
+    for r in range(N):
+        for s in range(N):
+            src, blks = B.mmsp_zigzag_plan_packed(T, N, r, s, cu_host=cu)
+            src_o, blks_o = orc.zigzag_plan_packed(T, N, r, s, cu)
+            got = [(b.q_row0, b.k_row0, b.q_pos0, b.k_pos0, b.n_q, b.n_k, b.mask) for b in blks]
+            want = [(b["q_row0"], b["k_row0"], b["q_pos0"], b["k_pos0"], b["n_q"], b["n_k"], b["mask"]) for b in blks_o]
+            assert src == src_o and got == want
+            dropped += len(orc.zigzag_plan_packed(T, N, r, s)[1]) - len(blks)
+    assert dropped > 0 or len(cu) == 2
+
+
 def test_layout_of_the_papers_example():
     got = [B.mmsp_zigzag_layout(8, 4, r)[1].tolist() for r in range(4)]
     assert got == [[0, 7], [1, 6], [2, 5], [3, 4]]

@@ -315,6 +315,56 @@ def test_ring_emulation_reassembles_the_unsharded_result(N, C, Hq, Hkv):
         np.testing.assert_allclose(got, ref, atol=1e-12)
 
 
+@pytest.mark.parametrize("T,N", [(8, 4), (48, 3), (64, 2)])
+def test_packed_plan_covers_exactly_the_visible_pairs(T, N):
+    """Brute force over every (query, key) token pair: the sub-blocks of the packed plan, with
+    the document test applied, see each causal same-document pair of the rank's rows exactly once."""
+    rng = np.random.default_rng(T + N)
+    cuts = np.sort(rng.choice(np.arange(1, T), size=3, replace=False))
+    cu = np.concatenate([[0], cuts, [T]]).astype(np.int32)
+    doc = orc.doc_of(np.arange(T), cu)
+    for r, pruned in [(r, p) for r in range(N) for p in (False, True)]:
+        _, l2g = orc.zigzag_layout(T, N, r)
+        count = np.zeros((len(l2g), T), dtype=np.int32)
+        for s in range(N):
+            src, blks = orc.zigzag_plan_packed(T, N, r, s, cu if pruned else None)
+            _, src_rows = orc.zigzag_layout(T, N, src)
+            assert len(blks) <= 3 and (pruned or len(blks) >= 2)
+            for blk in blks:
+                vis = orc.block_visibility(blk, cu)
+                qs = np.arange(blk["q_row0"], blk["q_row0"] + blk["n_q"])
+                ks = src_rows[blk["k_row0"]: blk["k_row0"] + blk["n_k"]]
+                assert np.array_equal(l2g[qs], blk["q_pos0"] + np.arange(blk["n_q"]))     # positions are the global ones
+                assert np.array_equal(ks, blk["k_pos0"] + np.arange(blk["n_k"]))
+                count[np.ix_(qs, ks)] += vis
+        want = (np.arange(T)[None, :] <= l2g[:, None]) & (doc[None, :] == doc[l2g][:, None])
+        assert np.array_equal(count, want.astype(np.int32))
+
+
+@pytest.mark.parametrize("with_docs", [True, False])
+def test_packed_ring_emulation_reassembles_the_unsharded_result(with_docs):
+    rng = np.random.default_rng(33)
+    N, C, Hq, Hkv, d = 3, 4, 4, 2, 5
+    T = 2 * N * C
+    cu = np.array([0, 3, 4, 13, 19, T], dtype=np.int32) if with_docs else None
+    Q, K, V, dO = _rand(rng, T, Hq, d), _rand(rng, T, Hkv, d), _rand(rng, T, Hkv, d), _rand(rng, T, Hq, d)
+    scale = 1 / math.sqrt(d)
+    O_ref, L_ref, dQ_ref, dK_ref, dV_ref = orc.causal_attention(Q, K, V, scale, cu_seqlens=cu, dO=dO)
+    O = np.zeros_like(O_ref); L = np.zeros_like(L_ref); dQ = np.zeros_like(Q)
+    dK = np.zeros_like(K); dV = np.zeros_like(V)
+    for r in range(N):
+        _, l2g = orc.zigzag_layout(T, N, r)
+        o, l = orc.ring_rank_fwd_packed(Q, K, V, N, r, scale, cu)
+        O[l2g], L[:, l2g] = o, l
+        dq, dk, dv = orc.ring_rank_bwd_packed(Q, K, V, dO[l2g], o, l, N, r, scale, cu)
+        dQ[l2g] = dq; dK += dk; dV += dv
+        if not with_docs:                                  # without documents the packed plan is the plain one, regrouped
+            o2, l2 = orc.ring_rank_fwd(Q, K, V, N, r, scale)
+            np.testing.assert_allclose(o, o2, atol=1e-12); np.testing.assert_allclose(l, l2, atol=1e-12)
+    for got, ref in [(O, O_ref), (L, L_ref), (dQ, dQ_ref), (dK, dK_ref), (dV, dV_ref)]:
+        np.testing.assert_allclose(got, ref, atol=1e-12)
+
+
 # ---------------------------------------------------------------- backward: finite differences
 @pytest.mark.parametrize("cu", [None, [0, 3, 10, 14]])
 def test_backward_matches_central_finite_differences(cu):

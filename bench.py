@@ -158,6 +158,11 @@ def main():
                          "N=8 with 16384-token chunks of the same 256K sequence")
     ap.add_argument("--rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layout", default="zigzag", choices=["zigzag", "contiguous"],
+                    help="zigzag workloads: contiguous = the plain ring layout (rank r holds tokens [r T/N, (r+1) T/N)), whose "
+                         "work grows with the rank, for comparison with the balanced both-ends layout")
+    ap.add_argument("--fwd-only", action="store_true",
+                    help="zigzag workloads: time the forward ring steps only (the long-prefill compute of the inference mode)")
     ap.add_argument("--packed", action="store_true",
                     help="zigzag workloads: the sequence is packed from documents (synth.packed_cu_seqlens) and the ring "
                          "steps run the sub-blocks of mmsp_zigzag_plan_packed under the document-causal mask, one stream")
@@ -212,11 +217,14 @@ def main():
     # ---- synthetic inputs, chunk by chunk (the full K/V never sit on the host in fp32 at once)
     k_zz = torch.empty(N, n, Hkv, d, dtype=torch.bfloat16, device=dev)
     v_zz = torch.empty_like(k_zz)
+    contiguous = args.layout == "contiguous"
+    chunks_of = (lambda r: (2 * r, 2 * r + 1)) if contiguous else (lambda r: (r, 2 * N - 1 - r))
+    plan = B.mmsp_contiguous_plan if contiguous else B.mmsp_zigzag_plan
     for r in range(N):
-        for half, c in enumerate((r, 2 * N - 1 - r)):
+        for half, c in enumerate(chunks_of(r)):
             k_zz[r, half * C:(half + 1) * C] = upload(synth.chunk("k", c, C, Hkv, d, cfg["sigma"], cfg["seed"]))
             v_zz[r, half * C:(half + 1) * C] = upload(synth.chunk("v", c, C, Hkv, d, cfg["sigma"], cfg["seed"]))
-    chunks = (rank, 2 * N - 1 - rank)
+    chunks = chunks_of(rank)
     q_host = np.concatenate([synth.chunk("q", c, C, Hq, d, cfg["sigma"], cfg["seed"]) for c in chunks])
     do_host = np.concatenate([synth.chunk("do", c, C, Hq, d, 1.0, cfg["seed"]) for c in chunks])
     q, d_o = upload(q_host), upload(do_host)
@@ -241,10 +249,13 @@ def main():
                              torch.empty_like(ws), ws_bytes)
 
     def one_pass():
-        ring.rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes, side=side)
+        ring.rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes, side=side,
+                          plan=plan)
+        if args.fwd_only:
+            return
         dq.zero_()
         ring.rank_backward(shape, T, N, rank, q, k_zz, v_zz, o_final, d_o, lse, delta, dq, dk_zz, dv_zz, ws=ws,
-                           ws_bytes=ws_bytes, side=side)
+                           ws_bytes=ws_bytes, side=side, plan=plan)
 
     if args.packed:
         print(json.dumps(bench_packed(args, cfg, torch, np, B, ring, synth, locals())))
@@ -260,9 +271,9 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
 
-    pairs = pairs_of_rank(N, C)
+    pairs = rank * n * n + n * (n + 1) // 2 if contiguous else pairs_of_rank(N, C)
     flops_fwd = 4 * d * Hq * pairs
-    flops_bwd = 10 * d * Hq * pairs
+    flops_bwd = 0 if args.fwd_only else 10 * d * Hq * pairs
     value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
 
     # ---- instrumented pass: HIP events around each kind of call (same stream the kernels run on)
@@ -271,7 +282,7 @@ def main():
         e0.record(); fn(); e1.record()
         return e0, e1
 
-    plans = [B.mmsp_zigzag_plan(T, N, rank, s) for s in range(N)]
+    plans = [plan(T, N, rank, s) for s in range(N)]
     kinds = {"fwd_step": [], "merge_cast": [], "delta": [], "bwd_dq": [], "bwd_dkdv": []}
     torch.cuda.synchronize()
     for _ in range(2):
@@ -286,6 +297,8 @@ def main():
     torch.cuda.synchronize()
 
     def blk_pairs(blk):
+        if blk.mask == B.MMSP_MASK_NONE:
+            return 0
         if blk.mask == B.MMSP_MASK_CAUSAL_DIAG:
             return blk.n_q * (blk.n_q + 1) // 2
         return blk.n_q * blk.n_k
@@ -322,11 +335,11 @@ def main():
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.fwd_only:
         from oracle import mmsp_oracle as orc
         rows = np.concatenate([np.linspace(0, C - 1, args.cpu_rows).astype(np.int64),
                                C + np.linspace(0, C - 1, args.cpu_rows).astype(np.int64)])
-        _, l2g = orc.zigzag_layout(T, N, rank)
+        l2g = np.arange(rank * n, (rank + 1) * n, dtype=np.int64) if contiguous else orc.zigzag_layout(T, N, rank)[1]
         K = np.empty((T, Hkv, d)); V = np.empty((T, Hkv, d))
         for c in range(2 * N):
             K[c * C:(c + 1) * C] = synth.chunk("k", c, C, Hkv, d, cfg["sigma"], cfg["seed"])
@@ -352,8 +365,9 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "frac_of_bf16_dense_peak": value / BF16_DENSE_PEAK_TFLOPS,
-        "config": {"workload": "%s: zigzag rank %d of N=%d, C=%d (T=%d), %d/%d heads, d=%d, bf16, fwd+bwd over all %d "
-                               "ring steps" % (args.config, rank, N, C, T, Hq, Hkv, d, N),
+        "config": {"workload": "%s: %s rank %d of N=%d, C=%d (T=%d), %d/%d heads, d=%d, bf16, %s over all %d "
+                               "ring steps" % (args.config, args.layout, rank, N, C, T, Hq, Hkv, d,
+                                               "forward only" if args.fwd_only else "fwd+bwd", N),
                    "streams": 1 if side is None else 2,
                    "pairs_per_head": pairs, "tflop_fwd": flops_fwd / 1e12, "tflop_bwd": flops_bwd / 1e12},
         "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown,

@@ -102,6 +102,15 @@ mmsp_status mmsp_zigzag_layout(int64_t T, int32_t N, int32_t rank,
 mmsp_status mmsp_zigzag_plan(int64_t T, int32_t N, int32_t rank, int32_t step,
                              int32_t* src_rank, mmsp_block* blk);
 
+/* The ring step of the plain (contiguous) RingAttention layout, the comparison figure's first
+ * row and the baseline the zigzag rule is measured against: rank r holds chunk r of N equal
+ * chunks; the block of rank src = (rank - step) mod N visits.  src == rank: all T/N rows,
+ * CAUSAL_DIAG; src < rank: FULL; src > rank: MMSP_MASK_NONE (the rank has nothing to do, which
+ * is the imbalance the paper describes: rank 0 idles after the first round).  INVALID_ARG if
+ * T <= 0, N <= 0, T % N != 0, or rank / step not in [0,N). */
+mmsp_status mmsp_contiguous_plan(int64_t T, int32_t N, int32_t rank, int32_t step,
+                                 int32_t* src_rank, mmsp_block* blk);
+
 /* The same ring step for a packed (variable-length) sequence whose document mask is given by
  * cu_seqlens on global positions -- Sec. 4.2 "MM-SP workflow" (token-level sharding of the
  * packed vision + text inputs from both ends).  A rank's local rows are two segments with

@@ -209,6 +209,16 @@ def zigzag_plan(T, N, rank, step):
     return dict(src=src, q_row0=C, n_q=C, k_row0=0, n_k=2 * C, q_pos0=0, k_pos0=0, mask=MASK_FULL)
 
 
+def contiguous_plan(T, N, rank, step):
+    """Plain RingAttention layout (the comparison figure's first row): rank r holds the
+    contiguous chunk r of N; at step `step` the block of rank src = (r - step) mod N visits.
+    Own block: causal; src < r: everything visible; src > r: nothing (the rank idles)."""
+    L = T // N
+    src = (rank - step) % N
+    mask = MASK_CAUSAL_DIAG if src == rank else (MASK_FULL if src < rank else MASK_NONE)
+    return dict(src=src, q_row0=0, n_q=L, k_row0=0, n_k=L, q_pos0=0, k_pos0=0, mask=mask)
+
+
 def zigzag_plan_packed(T, N, rank, step, cu_seqlens=None):
     """Ring step `step` of rank `rank` for a packed sequence (document mask from cu_seqlens on
     global positions): the local rows are two segments with positions chunk_r*C.. and

@@ -16,7 +16,7 @@ MMSP_OK, MMSP_ERR_INVALID_ARG, MMSP_ERR_UNSUPPORTED, MMSP_ERR_WORKSPACE_TOO_SMAL
 MMSP_MASK_FULL, MMSP_MASK_CAUSAL_DIAG, MMSP_MASK_NONE = 0, 1, 2
 MMSP_BF16, MMSP_F32 = 0, 1
 
-EXPORTS = ["mmsp_zigzag_layout", "mmsp_zigzag_plan", "mmsp_zigzag_plan_packed", "mmsp_2d_layout", "mmsp_workspace_bytes", "mmsp_attn_step_fwd",
+EXPORTS = ["mmsp_zigzag_layout", "mmsp_zigzag_plan", "mmsp_contiguous_plan", "mmsp_zigzag_plan_packed", "mmsp_2d_layout", "mmsp_workspace_bytes", "mmsp_attn_step_fwd",
            "mmsp_attn_merge", "mmsp_attn_delta", "mmsp_attn_step_bwd", "mmsp_last_error"]
 
 
@@ -56,6 +56,7 @@ _lib.mmsp_last_error.restype = ctypes.c_char_p
 _lib.mmsp_last_error.argtypes = []
 _lib.mmsp_zigzag_layout.argtypes = [_I64, _I32, _I32, ctypes.POINTER(_I32), ctypes.POINTER(_I64)]
 _lib.mmsp_zigzag_plan.argtypes = [_I64, _I32, _I32, _I32, ctypes.POINTER(_I32), ctypes.POINTER(MmspBlock)]
+_lib.mmsp_contiguous_plan.argtypes = [_I64, _I32, _I32, _I32, ctypes.POINTER(_I32), ctypes.POINTER(MmspBlock)]
 _lib.mmsp_zigzag_plan_packed.argtypes = [_I64, _I32, _I32, _I32, ctypes.POINTER(_I32), _I32, ctypes.POINTER(_I32),
                                          ctypes.POINTER(MmspBlock), ctypes.POINTER(_I32)]
 _lib.mmsp_2d_layout.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, ctypes.POINTER(Mmsp2dShare)]
@@ -107,6 +108,13 @@ def mmsp_zigzag_plan(T, N, rank, step):
     src = _I32()
     blk = MmspBlock()
     _check(_lib.mmsp_zigzag_plan(T, N, rank, step, ctypes.byref(src), ctypes.byref(blk)))
+    return src.value, blk
+
+
+def mmsp_contiguous_plan(T, N, rank, step):
+    src = _I32()
+    blk = MmspBlock()
+    _check(_lib.mmsp_contiguous_plan(T, N, rank, step, ctypes.byref(src), ctypes.byref(blk)))
     return src.value, blk
 
 

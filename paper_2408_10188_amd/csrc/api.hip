@@ -137,6 +137,19 @@ mmsp_status mmsp_zigzag_layout(int64_t T, int32_t N, int32_t rank, int32_t chunk
   return MMSP_OK;
 }
 
+mmsp_status mmsp_contiguous_plan(int64_t T, int32_t N, int32_t rank, int32_t step, int32_t* src_rank, mmsp_block* blk) {
+  if (T <= 0 || N <= 0 || T % N != 0) return fail(MMSP_ERR_INVALID_ARG, "T=%lld must be a positive multiple of N=%d", (long long)T, N);
+  if (rank < 0 || rank >= N || step < 0 || step >= N)
+    return fail(MMSP_ERR_INVALID_ARG, "rank=%d and step=%d must be in [0, %d)", rank, step, N);
+  if (src_rank == nullptr || blk == nullptr) return fail(MMSP_ERR_INVALID_ARG, "src_rank or blk is NULL");
+  const int32_t src = ((rank - step) % N + N) % N;
+  *src_rank = src;
+  memset(blk, 0, sizeof(*blk));
+  blk->n_q = T / N; blk->n_k = T / N;
+  blk->mask = src == rank ? MMSP_MASK_CAUSAL_DIAG : (src < rank ? MMSP_MASK_FULL : MMSP_MASK_NONE);
+  return MMSP_OK;
+}
+
 mmsp_status mmsp_zigzag_plan_packed(int64_t T, int32_t N, int32_t rank, int32_t step, const int32_t* cu_seqlens_host,
                                     int32_t n_docs, int32_t* src_rank, mmsp_block blks[4], int32_t* n_blocks) {
   mmsp_status st = check_zigzag(T, N, rank);

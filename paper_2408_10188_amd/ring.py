@@ -55,19 +55,22 @@ def _fork(side):
 
 
 def rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final=None, stream=0, fused_merge=True,
-                 o_part=None, lse_part=None, ws=None, ws_bytes=0, side=None):
+                 o_part=None, lse_part=None, ws=None, ws_bytes=0, side=None, plan=None):
     """All N forward steps of `rank`.  fused_merge=True merges in the step kernel's epilogue;
     otherwise every step writes (o_part, lse_part) and mmsp_attn_merge combines them.
     With `side` (fused merge only, launches on the current torch stream and on side.stream)
-    odd steps accumulate into the side lane and the final merge folds it in."""
+    odd steps accumulate into the side lane and the final merge folds it in.
+    `plan` (default mmsp_zigzag_plan) maps (T, N, rank, step) to (src, block); with
+    mmsp_contiguous_plan, q and k_zz[r] hold the contiguous chunk r instead of the zigzag pair."""
     n_rows = q.shape[0]
+    plan = plan or B.mmsp_zigzag_plan
     if side is not None and N > 1:
         main = _fork(side)
         # rows that no odd step reaches must still hold an empty partial result
         B.mmsp_attn_step_fwd(shape, B.make_block(0, n_rows, 0, 0, B.MMSP_MASK_NONE, 0, 0), q, k_zz[0], v_zz[0],
                              side.o_acc, side.lse, False, side.ws, side.ws_bytes, side.handle)
         for s in range(N):
-            src, blk = B.mmsp_zigzag_plan(T, N, rank, s)
+            src, blk = plan(T, N, rank, s)
             if s & 1:
                 B.mmsp_attn_step_fwd(shape, blk, q, k_zz[src], v_zz[src], side.o_acc, side.lse, True, side.ws,
                                      side.ws_bytes, side.handle)
@@ -78,7 +81,7 @@ def rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final=None, str
         B.mmsp_attn_merge(shape, 0, n_rows, o_acc, lse, side.o_acc, side.lse, o_final, stream=main.cuda_stream)
         return
     for s in range(N):
-        src, blk = B.mmsp_zigzag_plan(T, N, rank, s)
+        src, blk = plan(T, N, rank, s)
         if fused_merge or s == 0:
             B.mmsp_attn_step_fwd(shape, blk, q, k_zz[src], v_zz[src], o_acc, lse, s > 0, ws, ws_bytes, stream)
         else:
@@ -89,18 +92,19 @@ def rank_forward(shape, T, N, rank, q, k_zz, v_zz, o_acc, lse, o_final=None, str
 
 
 def rank_backward(shape, T, N, rank, q, k_zz, v_zz, o_final, d_o, lse, delta, dq, dk_zz, dv_zz, stream=0, ws=None,
-                  ws_bytes=0, side=None):
+                  ws_bytes=0, side=None, plan=None):
     """delta pre-pass, then all N backward steps of `rank`.  dq must be zero on entry.
     With `side` the dQ kernels run on the current torch stream and the dK/dV kernels on
-    side.stream (with side's workspace)."""
+    side.stream (with side's workspace).  `plan` as in rank_forward."""
     n_rows = q.shape[0]
+    plan = plan or B.mmsp_zigzag_plan
     if side is not None:
         import torch
         main = torch.cuda.current_stream()
         B.mmsp_attn_delta(shape, 0, n_rows, o_final, d_o, delta, stream=main.cuda_stream)
         side.stream.wait_stream(main)
         for s in range(N):
-            src, blk = B.mmsp_zigzag_plan(T, N, rank, s)
+            src, blk = plan(T, N, rank, s)
             B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, False, dq, None, None,
                                  False, ws, ws_bytes, main.cuda_stream)
             B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, False, None,
@@ -109,7 +113,7 @@ def rank_backward(shape, T, N, rank, q, k_zz, v_zz, o_final, d_o, lse, delta, dq
         return
     B.mmsp_attn_delta(shape, 0, n_rows, o_final, d_o, delta, stream=stream)
     for s in range(N):
-        src, blk = B.mmsp_zigzag_plan(T, N, rank, s)
+        src, blk = plan(T, N, rank, s)
         B.mmsp_attn_step_bwd(shape, blk, q, k_zz[src], v_zz[src], None, d_o, lse, delta, False, dq,
                              dk_zz[src], dv_zz[src], False, ws, ws_bytes, stream)
 

@@ -348,3 +348,39 @@ def test_zigzag_ring_over_packed_documents(dtype, N, C, d, cuts):
         dK_sum += prob.unzigzag(to_host64(dk)); dV_sum += prob.unzigzag(to_host64(dv))
         dK_ref += ref[3]; dV_ref += ref[4]
     assert max_abs(dK_sum, dK_ref) <= tol["g"] and max_abs(dV_sum, dV_ref) <= tol["g"]
+
+
+def test_contiguous_ring_layout():
+    """Plain ring layout through the same calls (mmsp_contiguous_plan): every rank's merged rows
+    equal the unsharded causal result; low ranks skip the rounds in which they see nothing."""
+    N, L, Hq, Hkv, d = 3, 160, 4, 2, 128
+    T = N * L
+    rng = np.random.default_rng(61)
+    g = lambda H, s: synth.bf16_round(rng.standard_normal((T, H, d), dtype=np.float32) * s)
+    Q, K, V, dO = g(Hq, 0.5), g(Hkv, 0.5), g(Hkv, 0.5), g(Hq, 1.0)
+    scale = 1 / math.sqrt(d)
+    ref = orc.causal_attention(Q.astype(np.float64), K.astype(np.float64), V.astype(np.float64), scale, dO=dO.astype(np.float64))
+    k_blk = to_dev(K, True).view(N, L, Hkv, d)
+    v_blk = to_dev(V, True).view(N, L, Hkv, d)
+    dK = np.zeros((T, Hkv, d)); dV = np.zeros((T, Hkv, d))
+    for r in range(N):
+        rows = slice(r * L, (r + 1) * L)
+        qd, dod = to_dev(Q[rows], True), to_dev(dO[rows], True)
+        shape = ring.shape_for(qd, k_blk, B.MMSP_BF16, L, scale)
+        o_acc = torch.empty(L, Hq, d, dtype=torch.float32, device=DEV)
+        lse = torch.empty(Hq, L, dtype=torch.float32, device=DEV)
+        o_final = torch.empty_like(qd)
+        delta, dq = torch.empty_like(lse), torch.zeros_like(o_acc)
+        dk = torch.zeros(N, L, Hkv, d, dtype=torch.float32, device=DEV)
+        dv = torch.zeros_like(dk)
+        ws_bytes = ring.workspace_bytes(shape, L, L)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+        ring.rank_forward(shape, T, N, r, qd, k_blk, v_blk, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes, plan=B.mmsp_contiguous_plan)
+        ring.rank_backward(shape, T, N, r, qd, k_blk, v_blk, o_final, dod, lse, delta, dq, dk, dv, ws=ws, ws_bytes=ws_bytes,
+                           plan=B.mmsp_contiguous_plan)
+        torch.cuda.synchronize()
+        errs = dict(o=max_abs(to_host64(o_acc), ref[0][rows]), lse=max_abs(to_host64(lse), ref[1][:, rows]),
+                    dq=max_abs(to_host64(dq), ref[2][rows]))
+        assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 and errs["dq"] <= 2e-2, (r, errs)
+        dK += to_host64(dk).reshape(T, Hkv, d); dV += to_host64(dv).reshape(T, Hkv, d)
+    assert max_abs(dK, ref[3]) <= 2e-2 and max_abs(dV, ref[4]) <= 2e-2

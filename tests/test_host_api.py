@@ -71,6 +71,20 @@ def test_packed_plan_pruning_matches_the_oracle(T, N, cu):
     assert dropped > 0 or len(cu) == 2
 
 
+@pytest.mark.parametrize("T,N", [(8, 4), (30, 3), (262144, 32)])
+def test_contiguous_plan_matches_the_oracle_bit_for_bit(T, N):
+    for r in range(N):
+        for s in range(N):
+            src, blk = B.mmsp_contiguous_plan(T, N, r, s)
+            ref = orc.contiguous_plan(T, N, r, s)
+            got = dict(src=src, q_row0=blk.q_row0, n_q=blk.n_q, k_row0=blk.k_row0, n_k=blk.n_k,
+                       q_pos0=blk.q_pos0, k_pos0=blk.k_pos0, mask=blk.mask)
+            assert got == ref
+    for bad in [(10, 4, 0, 0), (8, 4, 4, 0), (8, 4, 0, 4), (0, 4, 0, 0), (8, 0, 0, 0)]:
+        with pytest.raises(B.MmspError):
+            B.mmsp_contiguous_plan(*bad)
+
+
 def test_layout_of_the_papers_example():
     got = [B.mmsp_zigzag_layout(8, 4, r)[1].tolist() for r in range(4)]
     assert got == [[0, 7], [1, 6], [2, 5], [3, 4]]

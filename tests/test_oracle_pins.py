@@ -244,6 +244,31 @@ def test_plain_ring_imbalance_example():
         assert busy == int(rounds)
 
 
+@pytest.mark.parametrize("T,N", [(8, 4), (30, 3), (64, 8)])
+def test_contiguous_plan_reproduces_the_imbalance_and_the_unsharded_result(T, N):
+    """Plain ring layout: rank r has work in r+1 of N rounds and (r*L^2 + L(L+1)/2) pairs (the
+    paper's imbalance); merging its rounds still gives the rows of the unsharded result."""
+    rng = np.random.default_rng(T)
+    L, Hq, Hkv, d = T // N, 2, 1, 4
+    Q, K, V = _rand(rng, T, Hq, d), _rand(rng, T, Hkv, d), _rand(rng, T, Hkv, d)
+    scale = 1 / math.sqrt(d)
+    O_ref, L_ref = orc.causal_attention(Q, K, V, scale)[:2]
+    for r in range(N):
+        rows = np.arange(r * L, (r + 1) * L)
+        O = np.zeros((L, Hq, d)); Ls = np.full((Hq, L), -np.inf)
+        busy = pairs = 0
+        for s in range(N):
+            blk = orc.contiguous_plan(T, N, r, s)
+            src_rows = np.arange(blk["src"] * L, (blk["src"] + 1) * L)
+            vis = orc.block_visibility(blk)
+            assert np.array_equal(vis, orc.visible(rows, src_rows))       # the mask kind equals the definition on global positions
+            busy += bool(vis.any()); pairs += int(vis.sum())
+            O, Ls = orc.merge(O, Ls, *orc.step_fwd(Q[rows], K[src_rows], V[src_rows], blk, scale))
+        assert busy == r + 1 and pairs == r * L * L + L * (L + 1) // 2
+        np.testing.assert_allclose(O, O_ref[rows], atol=1e-12)
+        np.testing.assert_allclose(Ls, L_ref[:, rows], atol=1e-12)
+
+
 # ---------------------------------------------------------------- 2D-attention shares
 def test_two_d_share_matches_the_papers_example():
     for g, r, u, head, t0, t1, t2, t3, pairs in _read_rows("two_d_8_2x2.txt"):

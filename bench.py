@@ -101,6 +101,43 @@ def bench_ulysses(args, cfg, torch, np, B, ring, synth):
     }
 
 
+def bench_data_movement(args, torch, B):
+    """Row permutations around the attention path, bf16, T = 262144, 28 heads, d = 128."""
+    T, N, H, d, U = 262144, 32, 28, 128, 4
+    dev = "cuda:0"
+    x = torch.randn(T, H, d, device=dev).bfloat16()
+    shards = torch.empty(N, T // N, H, d, dtype=torch.bfloat16, device=dev)
+    back = torch.empty_like(x)
+    n_tok = T // U                                     # tokens per GPU of the all-to-all group
+    xs = x[:n_tok]
+    packed = torch.empty(U, n_tok, H // U, d, dtype=torch.bfloat16, device=dev)
+    unp = torch.empty_like(xs)
+    row_bytes, slice_bytes = H * d * 2, (H // U) * d * 2
+    ops = {"zigzag_gather": (lambda: B.mmsp_zigzag_gather(T, N, row_bytes, x, shards), 2 * x.numel() * 2),
+           "zigzag_scatter": (lambda: B.mmsp_zigzag_scatter(T, N, row_bytes, shards, back), 2 * x.numel() * 2),
+           "a2a_pack_heads": (lambda: B.mmsp_a2a_pack_heads(n_tok, U, slice_bytes, xs, packed), 2 * xs.numel() * 2),
+           "a2a_unpack_heads": (lambda: B.mmsp_a2a_unpack_heads(n_tok, U, slice_bytes, packed, unp), 2 * xs.numel() * 2)}
+    out = {}
+    for name, (fn, nbytes) in ops.items():
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        out[name] = {"ms": ms, "alg_bytes": nbytes, "gbs": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    assert torch.equal(back, x) and torch.equal(unp, xs)
+    worst = min(out, key=lambda k: out[k]["gbs"])
+    return {"metric": "HBM GB/s of the sharding kernels (read + written bytes / time)", "value": out[worst]["gbs"], "unit": "GB/s",
+            "n_gpus": 1, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "T=262144 x 28 heads x d=128 bf16: zigzag gather/scatter over N=32; head packing for U=4 on T/4 tokens"},
+            "roofline": {"kernel": worst, "bound": "hbm", "achieved": out[worst]["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": out[worst]["gbs"] / HBM_PEAK_GBS, "traffic": None},
+            "ops": out}
+
+
 def bench_packed(args, cfg, torch, np, B, ring, synth, env):
     """One zigzag rank over a packed sequence: document-causal mask on global positions."""
     N, C, Hq, Hkv, d, T, rank = (env[k] for k in ("N", "C", "Hq", "Hkv", "d", "T", "rank"))
@@ -168,6 +205,9 @@ def main():
                          "steps run the sub-blocks of mmsp_zigzag_plan_packed under the document-causal mask, one stream")
     ap.add_argument("--one-stream", action="store_true", help="all launches on one stream (no overlap of ring steps)")
     ap.add_argument("--cpu-rows", type=int, default=32, help="query rows per chunk in the oracle sample")
+    ap.add_argument("--data-movement", action="store_true",
+                    help="only time the HBM-bound sharding kernels at the 256K-token shapes (zigzag gather / scatter of Q, "
+                         "head packing around the all-to-all) and print one JSON line with their GB/s")
     ap.add_argument("--ceiling", action="store_true",
                     help="only run the stand-alone matrix-core ceiling probe (what MFMA + LDS + softmax-like work sustains "
                          "with trivial and with random operands) and print its lines")
@@ -199,6 +239,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 3}))
+        return
+
+    if args.data_movement:
+        print(json.dumps(bench_data_movement(args, torch, B)))
         return
 
     cfg = synth.CONFIGS[args.config]

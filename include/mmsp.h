@@ -151,6 +151,28 @@ typedef struct {
 mmsp_status mmsp_2d_layout(int64_t T, int32_t U, int32_t R, int32_t gpu, int32_t n_q_heads, int32_t n_kv_heads,
                            mmsp_2d_share* share);
 
+/* Token-level sharding of a whole sequence "from both ends" -- Sec. 4.2 "MM-SP workflow" (the
+ * second stage of the two-stage sharding).  seq (device) holds T rows of row_bytes bytes in
+ * sequence order (a row is one token's heads x d elements, any dtype); shards (device) holds
+ * the N ranks' local rows back to back, [N][2C] rows with C = T / (2N), rank r = chunk r then
+ * chunk 2N-1-r -- the order mmsp_zigzag_layout describes and the ring steps expect.  gather
+ * writes shards from seq, scatter writes seq from shards (e.g. O or dQ back in sequence order).
+ * One pass, 1 byte read + 1 byte written per byte.  row_bytes must be a positive multiple of
+ * 16, both pointers 16-byte aligned and the buffers must not overlap.  INVALID_ARG otherwise,
+ * or if T is not a positive multiple of 2N. */
+mmsp_status mmsp_zigzag_gather(int64_t T, int32_t N, int64_t row_bytes, const void* seq, void* shards, void* hip_stream);
+mmsp_status mmsp_zigzag_scatter(int64_t T, int32_t N, int64_t row_bytes, const void* shards, void* seq, void* hip_stream);
+
+/* Local re-grouping around the all-to-all of the head-sharded mode -- Sec. 4.2 (the all-to-all
+ * group distributes QKV by head and re-partitions along the sequence).  Before the exchange a
+ * GPU holds [n_tokens][U][slice_bytes] (its tokens, all heads as U head groups) and must send
+ * group u to peer u: pack writes y = [U][n_tokens][slice_bytes], one contiguous message per
+ * peer.  After the return exchange it holds [U][n_tokens][slice_bytes] (one message per head
+ * group) and unpack restores x = [n_tokens][U][slice_bytes].  slice_bytes = heads per group x
+ * d x element size, a positive multiple of 16; pointers 16-byte aligned, no overlap. */
+mmsp_status mmsp_a2a_pack_heads(int64_t n_tokens, int32_t U, int64_t slice_bytes, const void* x, void* y, void* hip_stream);
+mmsp_status mmsp_a2a_unpack_heads(int64_t n_tokens, int32_t U, int64_t slice_bytes, const void* y, void* x, void* hip_stream);
+
 /* Bytes of device workspace the step calls need for blocks of at most n_q_max x n_k_max rows
  * (0 for f32).  The bf16 kernels use it for token-contiguous (transposed) copies of tiles that
  * each call rebuilds before its main kernel and, in the backward, for partial dK/dV sums of

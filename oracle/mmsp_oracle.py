@@ -209,6 +209,33 @@ def zigzag_plan(T, N, rank, step):
     return dict(src=src, q_row0=C, n_q=C, k_row0=0, n_k=2 * C, q_pos0=0, k_pos0=0, mask=MASK_FULL)
 
 
+def zigzag_gather(x, N):
+    """[T, ...] in sequence order -> [N, 2C, ...]: every rank's local rows (chunk r | chunk 2N-1-r)."""
+    T = x.shape[0]
+    return np.stack([x[zigzag_layout(T, N, r)[1]] for r in range(N)])
+
+
+def zigzag_scatter(shards):
+    """Inverse of zigzag_gather."""
+    N, n = shards.shape[0], shards.shape[1]
+    out = np.empty((N * n, *shards.shape[2:]), dtype=shards.dtype)
+    for r in range(N):
+        out[zigzag_layout(N * n, N, r)[1]] = shards[r]
+    return out
+
+
+def a2a_pack_heads(x, U):
+    """[tokens, H, d] -> [U, tokens, H/U, d]: message u holds head group u of every local token."""
+    t, H, d = x.shape
+    return np.ascontiguousarray(x.reshape(t, U, H // U, d).transpose(1, 0, 2, 3))
+
+
+def a2a_unpack_heads(y):
+    """[U, tokens, H/U, d] (one message per head group) -> [tokens, H, d]."""
+    U, t, hh, d = y.shape
+    return np.ascontiguousarray(y.transpose(1, 0, 2, 3)).reshape(t, U * hh, d)
+
+
 def contiguous_plan(T, N, rank, step):
     """Plain RingAttention layout (the comparison figure's first row): rank r holds the
     contiguous chunk r of N; at step `step` the block of rank src = (r - step) mod N visits.

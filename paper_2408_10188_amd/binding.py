@@ -17,7 +17,8 @@ MMSP_MASK_FULL, MMSP_MASK_CAUSAL_DIAG, MMSP_MASK_NONE = 0, 1, 2
 MMSP_BF16, MMSP_F32 = 0, 1
 
 EXPORTS = ["mmsp_zigzag_layout", "mmsp_zigzag_plan", "mmsp_contiguous_plan", "mmsp_zigzag_plan_packed", "mmsp_2d_layout", "mmsp_workspace_bytes", "mmsp_attn_step_fwd",
-           "mmsp_attn_merge", "mmsp_attn_delta", "mmsp_attn_step_bwd", "mmsp_last_error"]
+           "mmsp_attn_merge", "mmsp_attn_delta", "mmsp_attn_step_bwd", "mmsp_zigzag_gather", "mmsp_zigzag_scatter",
+           "mmsp_a2a_pack_heads", "mmsp_a2a_unpack_heads", "mmsp_last_error"]
 
 
 class MmspShape(ctypes.Structure):
@@ -60,6 +61,10 @@ _lib.mmsp_contiguous_plan.argtypes = [_I64, _I32, _I32, _I32, ctypes.POINTER(_I3
 _lib.mmsp_zigzag_plan_packed.argtypes = [_I64, _I32, _I32, _I32, ctypes.POINTER(_I32), _I32, ctypes.POINTER(_I32),
                                          ctypes.POINTER(MmspBlock), ctypes.POINTER(_I32)]
 _lib.mmsp_2d_layout.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, ctypes.POINTER(Mmsp2dShare)]
+_lib.mmsp_zigzag_gather.argtypes = [_I64, _I32, _I64, _P, _P, _P]
+_lib.mmsp_zigzag_scatter.argtypes = [_I64, _I32, _I64, _P, _P, _P]
+_lib.mmsp_a2a_pack_heads.argtypes = [_I64, _I32, _I64, _P, _P, _P]
+_lib.mmsp_a2a_unpack_heads.argtypes = [_I64, _I32, _I64, _P, _P, _P]
 _lib.mmsp_workspace_bytes.restype = _SZ
 _lib.mmsp_workspace_bytes.argtypes = [ctypes.POINTER(MmspShape), _I64, _I64, _INT]
 _lib.mmsp_attn_step_fwd.argtypes = [ctypes.POINTER(MmspShape), ctypes.POINTER(MmspBlock), _P, _P, _P, _P, _P, _INT,
@@ -140,6 +145,22 @@ def mmsp_2d_layout(T, U, R, gpu, n_q_heads, n_kv_heads):
     share = Mmsp2dShare()
     _check(_lib.mmsp_2d_layout(T, U, R, gpu, n_q_heads, n_kv_heads, ctypes.byref(share)))
     return share
+
+
+def mmsp_zigzag_gather(T, N, row_bytes, seq, shards, stream=0):
+    _check(_lib.mmsp_zigzag_gather(T, N, row_bytes, _ptr(seq), _ptr(shards), stream or None))
+
+
+def mmsp_zigzag_scatter(T, N, row_bytes, shards, seq, stream=0):
+    _check(_lib.mmsp_zigzag_scatter(T, N, row_bytes, _ptr(shards), _ptr(seq), stream or None))
+
+
+def mmsp_a2a_pack_heads(n_tokens, U, slice_bytes, x, y, stream=0):
+    _check(_lib.mmsp_a2a_pack_heads(n_tokens, U, slice_bytes, _ptr(x), _ptr(y), stream or None))
+
+
+def mmsp_a2a_unpack_heads(n_tokens, U, slice_bytes, y, x, stream=0):
+    _check(_lib.mmsp_a2a_unpack_heads(n_tokens, U, slice_bytes, _ptr(y), _ptr(x), stream or None))
 
 
 def mmsp_workspace_bytes(shape, n_q_max, n_k_max, backward):

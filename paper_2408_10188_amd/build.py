@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmmsp.so")
 PROBE = os.path.join(HERE, "ceiling_probe")
-SOURCES = ["api.hip", "elementwise.hip", "ref_f32.hip", "transpose.hip", "fwd_bf16.hip", "bwd_bf16.hip", "bwd_dq_bf16.hip", "bwd_dkdv_bf16.hip"]
+SOURCES = ["api.hip", "elementwise.hip", "layout.hip", "ref_f32.hip", "transpose.hip", "fwd_bf16.hip", "bwd_bf16.hip", "bwd_dq_bf16.hip", "bwd_dkdv_bf16.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 EXTRA = os.environ.get("MMSP_EXTRA", "").split()
 FLAGS = [*EXTRA, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",

@@ -115,6 +115,13 @@ mmsp_status check_zigzag(int64_t T, int32_t N, int32_t rank) {
   return MMSP_OK;
 }
 
+mmsp_status check_rows_copy(int64_t row_bytes, const void* a, const void* b) {
+  if (row_bytes <= 0 || row_bytes % 16 != 0) return fail(MMSP_ERR_INVALID_ARG, "row size %lld must be a positive multiple of 16 bytes", (long long)row_bytes);
+  if (a == nullptr || b == nullptr || a == b) return fail(MMSP_ERR_INVALID_ARG, "source and destination must be distinct non-NULL buffers");
+  if (!aligned16(a) || !aligned16(b)) return fail(MMSP_ERR_INVALID_ARG, "buffers must be 16-byte aligned");
+  return MMSP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -285,6 +292,36 @@ mmsp_status mmsp_attn_merge(const mmsp_shape* shape, int64_t row0, int64_t n_row
                                           shape->lse_head_stride, shape->n_q_heads, shape->head_dim, (int)row0,
                                           (int)n_rows, reinterpret_cast<hipStream_t>(hip_stream)),
                        "merge");
+}
+
+mmsp_status mmsp_zigzag_gather(int64_t T, int32_t N, int64_t row_bytes, const void* seq, void* shards, void* hip_stream) {
+  mmsp_status st = check_zigzag(T, N, 0);
+  if (st != MMSP_OK) return st;
+  st = check_rows_copy(row_bytes, seq, shards);
+  if (st != MMSP_OK) return st;
+  return device_result(mmsp::launch_zigzag_gather(seq, shards, T, N, row_bytes, reinterpret_cast<hipStream_t>(hip_stream)), "zigzag_gather");
+}
+
+mmsp_status mmsp_zigzag_scatter(int64_t T, int32_t N, int64_t row_bytes, const void* shards, void* seq, void* hip_stream) {
+  mmsp_status st = check_zigzag(T, N, 0);
+  if (st != MMSP_OK) return st;
+  st = check_rows_copy(row_bytes, shards, seq);
+  if (st != MMSP_OK) return st;
+  return device_result(mmsp::launch_zigzag_scatter(shards, seq, T, N, row_bytes, reinterpret_cast<hipStream_t>(hip_stream)), "zigzag_scatter");
+}
+
+mmsp_status mmsp_a2a_pack_heads(int64_t n_tokens, int32_t U, int64_t slice_bytes, const void* x, void* y, void* hip_stream) {
+  if (n_tokens < 0 || U <= 0) return fail(MMSP_ERR_INVALID_ARG, "n_tokens=%lld must be >= 0 and U=%d > 0", (long long)n_tokens, U);
+  mmsp_status st = check_rows_copy(slice_bytes, x, y);
+  if (st != MMSP_OK) return st;
+  return device_result(mmsp::launch_swap_outer(x, y, n_tokens, U, slice_bytes, reinterpret_cast<hipStream_t>(hip_stream)), "a2a_pack_heads");
+}
+
+mmsp_status mmsp_a2a_unpack_heads(int64_t n_tokens, int32_t U, int64_t slice_bytes, const void* y, void* x, void* hip_stream) {
+  if (n_tokens < 0 || U <= 0) return fail(MMSP_ERR_INVALID_ARG, "n_tokens=%lld must be >= 0 and U=%d > 0", (long long)n_tokens, U);
+  mmsp_status st = check_rows_copy(slice_bytes, y, x);
+  if (st != MMSP_OK) return st;
+  return device_result(mmsp::launch_swap_outer(y, x, U, n_tokens, slice_bytes, reinterpret_cast<hipStream_t>(hip_stream)), "a2a_unpack_heads");
 }
 
 mmsp_status mmsp_attn_delta(const mmsp_shape* shape, int64_t row0, int64_t n_rows, const void* o_final,

@@ -111,6 +111,10 @@ int64_t bwd_dq_bf16_workspace_bytes(int Hkv, int64_t n_k);
 int64_t bwd_bf16_total_workspace_bytes(int Hq, int Hkv, int64_t n_q, int64_t n_k);
 hipError_t bwd_bf16_prepare(const StepArgs& a, BwdWorkspace& w, hipStream_t stream);
 
+hipError_t launch_zigzag_gather(const void* seq, void* shards, int64_t T, int N, int64_t row_bytes, hipStream_t stream);
+hipError_t launch_zigzag_scatter(const void* shards, void* seq, int64_t T, int N, int64_t row_bytes, hipStream_t stream);
+hipError_t launch_swap_outer(const void* src, void* dst, int64_t A, int64_t B, int64_t row_bytes, hipStream_t stream);
+
 hipError_t launch_fwd_f32(const StepArgs& a, hipStream_t stream);
 hipError_t launch_bwd_f32(const StepArgs& a, hipStream_t stream);
 hipError_t launch_fwd_bf16(const StepArgs& a, hipStream_t stream);

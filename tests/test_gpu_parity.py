@@ -384,3 +384,30 @@ def test_contiguous_ring_layout():
         assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 and errs["dq"] <= 2e-2, (r, errs)
         dK += to_host64(dk).reshape(T, Hkv, d); dV += to_host64(dv).reshape(T, Hkv, d)
     assert max_abs(dK, ref[3]) <= 2e-2 and max_abs(dV, ref[4]) <= 2e-2
+
+
+@pytest.mark.parametrize("T,N,H,d,dtype", [(8, 4, 1, 8, torch.bfloat16), (2304, 3, 7, 128, torch.bfloat16), (1024, 4, 4, 64, torch.float32)])
+def test_zigzag_gather_scatter_bit_exact(T, N, H, d, dtype):
+    x = torch.randn(T, H, d, device=DEV).to(dtype)
+    row_bytes = H * d * x.element_size()
+    shards = torch.empty(N, T // N, H, d, dtype=dtype, device=DEV)
+    B.mmsp_zigzag_gather(T, N, row_bytes, x, shards)
+    back = torch.empty_like(x)
+    B.mmsp_zigzag_scatter(T, N, row_bytes, shards, back)
+    torch.cuda.synchronize()
+    ref = orc.zigzag_gather(x.view(torch.int16 if dtype == torch.bfloat16 else torch.int32).cpu().numpy(), N)
+    got = shards.view(torch.int16 if dtype == torch.bfloat16 else torch.int32).cpu().numpy()
+    assert np.array_equal(got, ref) and torch.equal(back, x)
+
+
+@pytest.mark.parametrize("t,U,hh,d", [(5, 4, 2, 8), (1000, 4, 7, 128), (333, 7, 1, 128)])
+def test_a2a_head_packing_bit_exact(t, U, hh, d):
+    x = torch.randn(t, U * hh, d, device=DEV).bfloat16()
+    y = torch.empty(U, t, hh, d, dtype=torch.bfloat16, device=DEV)
+    B.mmsp_a2a_pack_heads(t, U, hh * d * 2, x, y)
+    back = torch.empty_like(x)
+    B.mmsp_a2a_unpack_heads(t, U, hh * d * 2, y, back)
+    torch.cuda.synchronize()
+    ref = orc.a2a_pack_heads(x.view(torch.int16).cpu().numpy(), U)
+    assert np.array_equal(y.view(torch.int16).cpu().numpy(), ref) and torch.equal(back, x)
+    assert np.array_equal(orc.a2a_unpack_heads(ref), x.view(torch.int16).cpu().numpy())

@@ -197,3 +197,16 @@ def test_workspace_size_and_rejection():
     with pytest.raises(B.MmspError) as e:
         B.mmsp_attn_step_fwd(shape, blk, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 100)
     assert e.value.status == B.MMSP_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_data_movement_calls_reject_bad_arguments():
+    ok = 4096                                          # any aligned non-NULL addresses: rejected before use
+    for fn, args in [(B._lib.mmsp_zigzag_gather, (10, 4, 256, ok, 2 * ok, None)),       # T not a multiple of 2N
+                     (B._lib.mmsp_zigzag_gather, (8, 4, 250, ok, 2 * ok, None)),        # row size not a multiple of 16
+                     (B._lib.mmsp_zigzag_scatter, (8, 4, 256, ok, ok, None)),           # in place
+                     (B._lib.mmsp_zigzag_scatter, (8, 4, 256, None, ok, None)),
+                     (B._lib.mmsp_a2a_pack_heads, (8, 0, 256, ok, 2 * ok, None)),
+                     (B._lib.mmsp_a2a_pack_heads, (8, 2, 256, ok + 8, 2 * ok, None)),   # misaligned
+                     (B._lib.mmsp_a2a_unpack_heads, (-1, 2, 256, ok, 2 * ok, None))]:
+        assert fn(*args) == B.MMSP_ERR_INVALID_ARG
+        assert B.mmsp_last_error() != ""

@@ -462,3 +462,42 @@ def test_delta_is_rowwise_dot():
     for i in range(5):
         for h in range(3):
             assert abs(D[h, i] - sum(dO[i, h, c] * O[i, h, c] for c in range(4))) < 1e-14
+
+
+# ---------------------------------------------------------------- data movement around attention
+def test_zigzag_gather_matches_the_papers_example_and_inverts():
+    """8 tokens / 4 ranks: shards are {0,7},{1,6},{2,5},{3,4} (the golden example); scatter inverts
+    gather for any N, and gathering positions gives each rank's local_to_global map."""
+    x = np.arange(8)
+    rows = [[int(t0), int(t1)] for _, t0, t1, _ in _read_rows("zigzag_8_4.txt")]
+    assert orc.zigzag_gather(x, 4).tolist() == rows
+    rng = np.random.default_rng(3)
+    for T, N in [(8, 4), (48, 3), (64, 1)]:
+        x = rng.standard_normal((T, 3, 2))
+        g = orc.zigzag_gather(x, N)
+        assert g.shape == (N, T // N, 3, 2) and np.array_equal(orc.zigzag_scatter(g), x)
+        pos = orc.zigzag_gather(np.arange(T), N)
+        for r in range(N):
+            assert np.array_equal(pos[r], orc.zigzag_layout(T, N, r)[1])
+
+
+def test_a2a_head_packing_is_the_head_to_sequence_exchange():
+    """Brute force: after packing on U GPUs, delivering message u of GPU g to GPU u and
+    concatenating by source, GPU u holds head group u of the whole sequence; the return trip
+    (messages per head group, unpack) restores the original token-sharded tensor."""
+    rng = np.random.default_rng(4)
+    U, t, H, d = 4, 5, 8, 3
+    full = rng.standard_normal((U * t, H, d))
+    local = [full[g * t:(g + 1) * t] for g in range(U)]                 # token-sharded, all heads
+    packed = [orc.a2a_pack_heads(x, U) for x in local]
+    for x, y in zip(local, packed):                                     # element by element
+        for u in range(U):
+            for i in range(t):
+                assert np.array_equal(y[u, i], x[i, u * (H // U):(u + 1) * (H // U)])
+    hh = H // U
+    for u in range(U):
+        recv = np.concatenate([packed[g][u] for g in range(U)])         # all-to-all: message u of every GPU, by source
+        assert np.array_equal(recv, full[:, u * hh:(u + 1) * hh])
+    for g in range(U):
+        back = np.stack([full[g * t:(g + 1) * t, u * hh:(u + 1) * hh] for u in range(U)])   # one message per head group
+        assert np.array_equal(orc.a2a_unpack_heads(back), local[g])

@@ -52,9 +52,11 @@ def test_tiny_fp32_rank0_fwd_merge_bwd():
     _check_rank(prob, 1, TOL_F32)
 
 
-@pytest.mark.parametrize("Hq,Hkv,N,C", [(4, 2, 2, 160), (7, 1, 3, 96), (2, 2, 1, 200)])
+@pytest.mark.parametrize("Hq,Hkv,N,C", [(4, 2, 2, 160), (7, 1, 3, 96), (2, 2, 1, 200), (6, 3, 2, 96), (8, 8, 2, 64), (32, 16, 1, 96)])
 def test_bf16_ring_small_ragged(Hq, Hkv, N, C):
-    """bf16 matrix-core path: several 128-row / 64-key tiles plus ragged tails, every rank."""
+    """bf16 matrix-core path: several 128-row / 64-key tiles plus ragged tails, every rank.  The
+    head counts cover both workgroup orders (KV heads that divide the 8 XCDs and that do not)
+    and group sizes 1, 2 and 7."""
     cfg = dict(dtype="bf16", Hq=Hq, Hkv=Hkv, d=128, N=N, C=C, sigma=0.5, seed=3)
     prob = RankProblem(cfg)
     for r in range(N):

@@ -187,7 +187,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="long", choices=["cfg3", "long", "ulysses", "2d"],
                     help="long (default, the headline workload) and cfg3: one zigzag rank, fwd+bwd; ulysses: "
                          "head-shard mode, 7/1 heads over the whole packed 256K sequence, fwd+bwd in one step; "

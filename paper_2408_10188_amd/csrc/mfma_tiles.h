@@ -33,11 +33,6 @@ __device__ __forceinline__ u32x4 mk4(uint32_t a, uint32_t b, uint32_t c, uint32_
   return r;
 }
 
-// acc + lo + hi of a packed bf16 pair (v_dot2c_f32_bf16 against (1, 1))
-__device__ __forceinline__ float add_pair(uint32_t packed, float acc) {
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
-}
-
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   f32x2 x = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
@@ -54,11 +49,6 @@ constexpr int kTileBytes = 64 * 128 * 2;     // 16 KiB, both layouts
 __device__ __forceinline__ int tile_n_offset(int row, int chunk /*0..15*/) {
   return row * 256 + ((chunk ^ (row & 15)) << 4);
 }
-// A operand for rows [rb*32, rb*32+32), k-step ks (d = ks*16 .. +16)
-__device__ __forceinline__ u32x4 tile_n_read(const char* tile, int rb, int ks, int lane) {
-  const int row = rb * 32 + (lane & 31);
-  return *reinterpret_cast<const u32x4*>(tile + tile_n_offset(row, ks * 2 + (lane >> 5)));
-}
 
 // ---------------------------------------------------------------------------------------
 // TileT: the same 64x128 tile transposed, [128 d][64 token slots].  Token t of the tile sits
@@ -70,11 +60,6 @@ __device__ __forceinline__ u32x4 tile_n_read(const char* tile, int rb, int ks, i
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int tile_t_offset(int d, int chunk /*0..7*/) {
   return (d >> 1) * 256 + (((d ^ (d >> 3)) & 1) << 7) + (((chunk ^ (d >> 4) ^ (d >> 1)) & 7) << 4);
-}
-// A operand for d rows [db*32, db*32+32), k-step g (tokens 16g .. 16g+16 in permuted order)
-__device__ __forceinline__ u32x4 tile_t_read(const char* tile, int db, int g, int lane) {
-  const int d = db * 32 + (lane & 31);
-  return *reinterpret_cast<const u32x4*>(tile + tile_t_offset(d, g * 2 + (lane >> 5)));
 }
 
 // Staging registers for one 64x128 tile and 256 threads: thread t owns the token group
@@ -98,30 +83,6 @@ __device__ __forceinline__ void tile_load(TileRegs& t, const uint16_t* base, int
     const int row = min(row0 + tok + r, n_rows - 1);
     t.r[r] = *reinterpret_cast<const u32x4*>(base + (int64_t)row * row_stride + dc * 8);
   }
-}
-
-// Same loads with the addressing split into a wavefront-uniform tile pointer and per-lane
-// 32-bit byte offsets that do not change from tile to tile (no per-tile address arithmetic).
-struct TileOffs { uint32_t o[4]; };
-
-__device__ __forceinline__ TileOffs tile_offsets(int64_t row_stride, int rows_left /* clamp: rows >= this repeat the last */,
-                                                 int tid) {
-  const int tok = stage_kg(tid) * 4, dc = tid & 15;
-  TileOffs t;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) t.o[r] = (uint32_t)(min(tok + r, rows_left - 1) * (int)row_stride * 2 + dc * 16);
-  return t;
-}
-
-__device__ __forceinline__ void tile_load(TileRegs& t, const char* tile_ptr /* uniform */, const TileOffs& off) {
-#pragma unroll
-  for (int r = 0; r < 4; ++r) t.r[r] = *reinterpret_cast<const u32x4*>(tile_ptr + off.o[r]);
-}
-
-__device__ __forceinline__ void tile_store_n(const TileRegs& t, char* tile, int tid) {
-  const int tok = stage_kg(tid) * 4, dc = tid & 15;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) *reinterpret_cast<u32x4*>(tile + tile_n_offset(tok + r, dc)) = t.r[r];
 }
 
 __device__ __forceinline__ uint32_t comp(const u32x4& v, int i) { return v[i]; }   // i constant after unrolling

@@ -79,9 +79,11 @@ typedef struct {
                                 consecutive positions.  Used by CAUSAL_DIAG and cu_seqlens */
   int32_t mask;              /* mmsp_mask                                                  */
   int32_t n_docs;            /* number of documents in cu_seqlens (0 when it is NULL)      */
-  const int32_t* cu_seqlens; /* device, [n_docs + 1], ascending, [0] = 0; NULL = one
+  const int32_t* cu_seqlens; /* device, [n_docs + 1], ascending, [0] >= 0; NULL = one
                                 document.  A pair is visible only if both positions fall
-                                in the same document (packed variable-length inputs).     */
+                                in the same document [cu[k], cu[k+1]) (packed variable-
+                                length inputs); positions below cu[0] or from cu[n_docs]
+                                on belong to no document and see nothing.                  */
 } mmsp_block;
 
 /* Zigzag ("both ends") sharding -- Sec. 4.2 "MM-SP workflow": the sequence is cut into 2N

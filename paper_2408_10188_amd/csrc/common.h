@@ -57,7 +57,7 @@ __device__ __forceinline__ void key_interval_of_row(const StepArgs& a, int i, in
     int L = 0, R = a.n_docs;          // invariant: cu[L] <= p (if p >= 0) < cu[R] (if inside)
     // positions outside every document see nothing; the empty intervals are chosen so that
     // lo and hi stay non-decreasing in the row index
-    if (p < 0) { lo = 0; hi = -1; return; }
+    if (p < a.cu[0]) { lo = 0; hi = -1; return; }
     if (p >= a.cu[a.n_docs]) { lo = a.n_k; hi = a.n_k - 1; return; }
     while (R - L > 1) { int m = (L + R) >> 1; if (a.cu[m] <= p) L = m; else R = m; }
     lo_pos = max(lo_pos, a.cu[L]);
@@ -75,7 +75,7 @@ __device__ __forceinline__ void row_interval_of_key(const StepArgs& a, int j, in
   if (a.mask == 1) lo_pos = p;
   if (a.cu != nullptr) {
     int L = 0, R = a.n_docs;
-    if (p < 0) { lo = 0; hi = -1; return; }
+    if (p < a.cu[0]) { lo = 0; hi = -1; return; }
     if (p >= a.cu[a.n_docs]) { lo = a.n_q; hi = a.n_q - 1; return; }
     while (R - L > 1) { int m = (L + R) >> 1; if (a.cu[m] <= p) L = m; else R = m; }
     lo_pos = max(lo_pos, a.cu[L]);

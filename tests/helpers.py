@@ -104,7 +104,8 @@ def max_abs(a, b):
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
     both_inf = np.isinf(a) & np.isinf(b) & (np.sign(a) == np.sign(b))
-    diff = np.where(both_inf, 0.0, np.abs(a - b))
+    with np.errstate(invalid="ignore"):          # inf - inf of matching infinities, replaced just below
+        diff = np.where(both_inf, 0.0, np.abs(a - b))
     return float(np.nanmax(diff)) if diff.size else 0.0
 
 

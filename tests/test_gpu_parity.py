@@ -413,3 +413,28 @@ def test_a2a_head_packing_bit_exact(t, U, hh, d):
     ref = orc.a2a_pack_heads(x.view(torch.int16).cpu().numpy(), U)
     assert np.array_equal(y.view(torch.int16).cpu().numpy(), ref) and torch.equal(back, x)
     assert np.array_equal(orc.a2a_unpack_heads(ref), x.view(torch.int16).cpu().numpy())
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_step_blocks(seed):
+    """Seeded random sub-blocks: sizes around the 32 / 64 / 128 / 256-row tile edges, random
+    offsets into the tensors, positions that put the causal diagonal anywhere, optional random
+    documents (some positions outside every document), random head grouping."""
+    rng = np.random.default_rng(1000 + seed)
+    edges = np.array([1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 513])
+    n_q, n_k = int(rng.choice(edges)), int(rng.choice(edges))
+    q_row0, k_row0 = int(rng.integers(0, 70)), int(rng.integers(0, 70))
+    Hkv = int(rng.choice([1, 2, 3]))
+    Hq = Hkv * int(rng.choice([1, 2, 4]))
+    mask = int(rng.choice([B.MMSP_MASK_CAUSAL_DIAG, B.MMSP_MASK_CAUSAL_DIAG, B.MMSP_MASK_FULL]))
+    q_pos0, k_pos0 = int(rng.integers(0, 400)), int(rng.integers(0, 400))
+    cu = None
+    if rng.random() < 0.6:
+        hi = max(q_pos0 + n_q, k_pos0 + n_k)
+        cuts = np.unique(rng.integers(0, hi + 40, size=int(rng.integers(1, 6))))
+        cu = [int(x) for x in cuts]
+        if len(cu) < 2:
+            cu = [0] + cu if cu[0] > 0 else cu + [hi]
+    blk = dict(q_row0=q_row0, n_q=n_q, k_row0=k_row0, n_k=n_k, mask=mask, q_pos0=q_pos0, k_pos0=k_pos0)
+    _run_step(True, Hq, Hkv, 128, q_row0 + n_q + int(rng.integers(0, 9)), k_row0 + n_k + int(rng.integers(0, 9)), blk, cu=cu,
+              seed=2000 + seed)

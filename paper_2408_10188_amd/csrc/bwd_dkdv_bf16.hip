@@ -32,9 +32,9 @@ __device__ __forceinline__ void dma4(const char* gptr, char* lds_wave_base) {
 
 // kMask = false: the host has checked that every (query, key) pair of the block is visible and
 // that n_q is a multiple of the tile length, so no tile needs masking.
-// nsplit > 1: the (head, query tile) sequence of every key tile is cut into nsplit contiguous
-// ranges, one workgroup each, which store their partial dK / dV into w.partial for
-// dkdv_reduce_kernel to sum (used when one workgroup per key tile would leave CUs idle).
+// nsplit > 1: the (query tile, head) sequence of every key tile is dealt out to nsplit
+// workgroups, which store their partial dK / dV into w.partial for dkdv_reduce_kernel to sum
+// (used when one workgroup per key tile would leave CUs idle or unevenly loaded).
 template <bool kMask>
 __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWorkspace w, int n_kt, int xcd_per_kv,
                                                                        int nsplit) {
@@ -84,12 +84,14 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   w_hi_min = __builtin_amdgcn_readfirstlane(w_hi_min);
   const int qt0 = t_lo / kBQ, qt1 = t_hi >= t_lo ? t_hi / kBQ : qt0 - 1;
   const int ntiles = qt1 - qt0 + 1;
-  // this workgroup's range [it0, it0 + niter) of the (head of the group, query tile) sequence
-  int it0 = 0, niter = 0;
+  // this workgroup's share of the (query tile, head of the group) sequence: elements split,
+  // split + nsplit, ...  (interleaved rather than contiguous, so that the workgroups of a key
+  // tile, and of neighbouring key tiles, walk the Q / dO tiles at the same place and pace and
+  // share them in L2)
+  int it0 = split, niter = 0;
   if (ntiles > 0) {
     const int total = ntiles * a.group;
-    it0 = (int)((int64_t)total * split / nsplit);
-    niter = (int)((int64_t)total * (split + 1) / nsplit) - it0;
+    niter = total > split ? (total - split + nsplit - 1) / nsplit : 0;
   }
   // Sequence order: query tiles from the last visible one downwards, the heads of the group
   // inside a tile.  Under a causal or document mask the key tiles that share an XCD see query
@@ -110,13 +112,15 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   const int64_t q_head_step = (int64_t)a.q_hs * 2, do_head_step = 256;
   const int64_t img_head_step = (int64_t)w.n_qtiles * kImageBytes, st_head_step = (int64_t)w.n_qtiles * kBQ * 4;
   const int gm1 = a.group - 1;
-  auto advance = [&](Cursor& cu) {
-    if (++cu.hg == a.group) {                            // next (lower) query tile, first head of the group
-      cu.hg = 0; --cu.qt;
-      cu.q -= gm1 * q_head_step + q_tile_bytes; cu.d_o -= gm1 * do_head_step + do_tile_bytes;
-      cu.img -= gm1 * img_head_step + kImageBytes; cu.st -= gm1 * st_head_step + kBQ * 4;
-    } else {
-      cu.q += q_head_step; cu.d_o += do_head_step; cu.img += img_head_step; cu.st += st_head_step;
+  auto advance = [&](Cursor& cu) {                       // nsplit elements further in the sequence
+    for (int j = 0; j < nsplit; ++j) {
+      if (++cu.hg == a.group) {                          // next (lower) query tile, first head of the group
+        cu.hg = 0; --cu.qt;
+        cu.q -= gm1 * q_head_step + q_tile_bytes; cu.d_o -= gm1 * do_head_step + do_tile_bytes;
+        cu.img -= gm1 * img_head_step + kImageBytes; cu.st -= gm1 * st_head_step + kBQ * 4;
+      } else {
+        cu.q += q_head_step; cu.d_o += do_head_step; cu.img += img_head_step; cu.st += st_head_step;
+      }
     }
   };
   Cursor fc;                                             // tile whose copies are being issued
@@ -206,7 +210,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   // wavefront waits for its own copies of it first).
   auto tile_body = [&](int it, char* cur, float* stat, char* oth, float* ostat) {
     const int q0 = cur_qt * kBQ;
-    if (++cur_hg == a.group) { cur_hg = 0; --cur_qt; }
+    cur_hg += nsplit;
+    while (cur_hg >= a.group) { cur_hg -= a.group; --cur_qt; }
     const bool need_mask = kMask && (q0 < w_lo_max || q0 + kBQ - 1 > w_hi_min);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -376,12 +381,12 @@ hipError_t launch_bwd_dkdv_bf16(const StepArgs& a, const BwdWorkspace& w, hipStr
   const int n_kt = (a.n_k + kKeys - 1) / kKeys;
   // One workgroup per (key tile, KV head) fills the chip only if there are about as many as
   // CUs; with fewer, cut every key tile's query sequence into ranges.
-  static int n_cu = 0;
+  static int cu_of_device[64] = {};                     // 0 = not asked yet; the count never changes for a device
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64) n_cu = cu_of_device[dev];
   if (n_cu == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-      v = kSplitMaxBlocks;
-    n_cu = v;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = kSplitMaxBlocks / 2;
+    if (dev >= 0 && dev < 64) cu_of_device[dev] = n_cu;
   }
   // With every pair visible all key tiles carry the same work and one round of workgroups is
   // best; under a mask the work per key tile varies (by 2x across a causal block), so aim for

@@ -210,3 +210,24 @@ def test_data_movement_calls_reject_bad_arguments():
                      (B._lib.mmsp_a2a_unpack_heads, (-1, 2, 256, ok, 2 * ok, None))]:
         assert fn(*args) == B.MMSP_ERR_INVALID_ARG
         assert B.mmsp_last_error() != ""
+
+
+def test_header_is_plain_c_and_usable_from_a_c_program(tmp_path):
+    """gcc -std=c99 compiles a client of include/mmsp.h; run against the built library it gets
+    the same integers as the Python binding."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    exe = tmp_path / "c_abi_check"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "c_abi_check.c"), "-o", str(exe), "-ldl"], check=True)
+    out = subprocess.run([str(exe), B.LIB_PATH], check=True, capture_output=True, text=True).stdout.split("\n")
+    ids, l2g = B.mmsp_zigzag_layout(8, 4, 1)
+    assert out[0] == "layout %d %d %d %d" % (ids[0], ids[1], l2g[0], l2g[1])
+    src, blk = B.mmsp_zigzag_plan(262144, 32, 0, 1)
+    assert out[1] == "plan %d %d %d %d %d %d" % (src, blk.q_row0, blk.n_q, blk.k_row0, blk.n_k, blk.mask)
+    sh = B.mmsp_2d_layout(262144, 4, 8, 13, 28, 4)
+    assert out[2] == "2d %d %d %d %d %d %d %d" % (sh.head_rank, sh.ring_rank, sh.q_head0, sh.n_q_heads, sh.kv_head0, sh.n_kv_heads, sh.chunk_len)
+    assert out[3] == "ws %d" % (4 * 128 * 16384)
+    assert out[4] == "bad %d message" % B.MMSP_ERR_INVALID_ARG

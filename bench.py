@@ -26,6 +26,24 @@ BF16_DENSE_PEAK_TFLOPS = 2500.0      # MI355X published dense bf16 MFMA peak
 HBM_PEAK_GBS = 8000.0
 
 
+def sample_clock_and_power(seconds, out):
+    """Samples rocm-smi (shader clock in MHz, socket power in W) for about `seconds` in a side
+    thread while passes run; appends (sclk_mhz, watts) tuples to out.  Best effort: leaves out
+    empty if the tool is missing or prints something else."""
+    import re
+    import subprocess
+    end = time.time() + seconds
+    while time.time() < end:
+        try:
+            txt = subprocess.run(["rocm-smi", "--showclocks", "--showpower"], capture_output=True, text=True, timeout=5).stdout
+        except Exception:
+            return
+        m = re.search(r"sclk clock level[^(]*\((\d+)Mhz\)", txt)
+        w = re.search(r"Power \(W\):\s*([0-9.]+)", txt)
+        if m:
+            out.append((int(m.group(1)), float(w.group(1)) if w else None))
+
+
 def pairs_of_rank(N, C):
     """Visible (query, key) pairs per query head for any rank of the zigzag layout: 2NC^2 + C."""
     return 2 * N * C * C + C
@@ -195,6 +213,7 @@ def main():
                          "N=8 with 16384-token chunks of the same 256K sequence")
     ap.add_argument("--rank", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-clock-sample", action="store_true", help="skip the 2 s of extra passes during which rocm-smi is polled")
     ap.add_argument("--layout", default="zigzag", choices=["zigzag", "contiguous"],
                     help="zigzag workloads: contiguous = the plain ring layout (rank r holds tokens [r T/N, (r+1) T/N)), whose "
                          "work grows with the rank, for comparison with the balanced both-ends layout")
@@ -315,6 +334,18 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
 
+    # shader clock and socket power under this load: a couple of seconds of extra passes with rocm-smi polled beside them
+    clock_samples = []
+    if not args.no_clock_sample:
+        import threading
+        th = threading.Thread(target=sample_clock_and_power, args=(2.0, clock_samples))
+        th.start()
+        t_end = time.time() + 2.2
+        while time.time() < t_end:
+            one_pass()
+            torch.cuda.synchronize()
+        th.join()
+
     pairs = rank * n * n + n * (n + 1) // 2 if contiguous else pairs_of_rank(N, C)
     flops_fwd = 4 * d * Hq * pairs
     flops_bwd = 0 if args.fwd_only else 10 * d * Hq * pairs
@@ -415,6 +446,12 @@ def main():
                    "streams": 1 if side is None else 2,
                    "pairs_per_head": pairs, "tflop_fwd": flops_fwd / 1e12, "tflop_bwd": flops_bwd / 1e12},
         "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown,
+        "clock_under_load": None if not clock_samples else {
+            "sclk_mhz_min_mean_max": [min(c for c, _ in clock_samples), sum(c for c, _ in clock_samples) / len(clock_samples),
+                                      max(c for c, _ in clock_samples)],
+            "socket_power_w_mean": (sum(w for _, w in clock_samples if w) / max(1, sum(1 for _, w in clock_samples if w))) or None,
+            "samples": len(clock_samples),
+            "note": "rocm-smi polled while extra passes of the same workload run after the timed region"},
     }
     print(json.dumps(out))
 

@@ -38,22 +38,26 @@ MASK_NONE = 2         # nothing visible
 # visibility (Sec. 4.2: causal attention; packed variable-length inputs, Sec. 4.1 end)
 # --------------------------------------------------------------------------------------
 def doc_of(pos, cu_seqlens):
-    """Index of the document (interval [cu[k], cu[k+1])) that holds each position."""
+    """Index of the document (interval [cu[k], cu[k+1])) that holds each position; -1 for a
+    position below cu[0] or from cu[-1] on, which belongs to no document."""
     pos = np.asarray(pos, dtype=np.int64)
     if cu_seqlens is None:
         return np.zeros_like(pos)
     cu = np.asarray(cu_seqlens, dtype=np.int64)
-    return np.searchsorted(cu, pos, side="right") - 1
+    doc = np.searchsorted(cu, pos, side="right") - 1
+    return np.where(pos >= cu[-1], -1, doc)
 
 
 def visible(q_pos, k_pos, cu_seqlens=None):
     """Boolean [nq, nk]: key j is visible to query i iff k_pos[j] <= q_pos[i] and both
-    lie in the same document."""
+    lie in the same document (a position outside every document sees nothing and is seen
+    by nothing)."""
     q_pos = np.asarray(q_pos, dtype=np.int64)
     k_pos = np.asarray(k_pos, dtype=np.int64)
     vis = k_pos[None, :] <= q_pos[:, None]
     if cu_seqlens is not None:
-        vis &= doc_of(q_pos, cu_seqlens)[:, None] == doc_of(k_pos, cu_seqlens)[None, :]
+        qd, kd = doc_of(q_pos, cu_seqlens), doc_of(k_pos, cu_seqlens)
+        vis &= (qd[:, None] == kd[None, :]) & (qd[:, None] >= 0)
     return vis
 
 
@@ -290,7 +294,8 @@ def block_visibility(blk, cu_seqlens=None):
     if blk["mask"] == MASK_FULL:
         vis = np.ones((nq, nk), dtype=bool)
         if cu_seqlens is not None:
-            vis &= doc_of(q_pos, cu_seqlens)[:, None] == doc_of(k_pos, cu_seqlens)[None, :]
+            qd, kd = doc_of(q_pos, cu_seqlens), doc_of(k_pos, cu_seqlens)
+            vis &= (qd[:, None] == kd[None, :]) & (qd[:, None] >= 0)
         return vis
     return visible(q_pos, k_pos, cu_seqlens)
 

@@ -415,7 +415,7 @@ def test_a2a_head_packing_bit_exact(t, U, hh, d):
     assert np.array_equal(orc.a2a_unpack_heads(ref), x.view(torch.int16).cpu().numpy())
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(64))
 def test_random_step_blocks(seed):
     """Seeded random sub-blocks: sizes around the 32 / 64 / 128 / 256-row tile edges, random
     offsets into the tensors, positions that put the causal diagonal anywhere, optional random

@@ -501,3 +501,28 @@ def test_a2a_head_packing_is_the_head_to_sequence_exchange():
     for g in range(U):
         back = np.stack([full[g * t:(g + 1) * t, u * hh:(u + 1) * hh] for u in range(U)])   # one message per head group
         assert np.array_equal(orc.a2a_unpack_heads(back), local[g])
+
+
+def test_positions_outside_every_document_see_nothing():
+    """cu_seqlens that does not cover every position: a pair is visible only if one document
+    [cu[k], cu[k+1]) holds both positions -- checked by plain loops over documents, for the
+    causal and for the full mask kind, and through the attention result (rows outside every
+    document come out empty: O = 0, LSE = -inf)."""
+    cu = [3, 7, 8, 15]
+    pos = np.arange(0, 20)
+    def same_doc(a, b):
+        return any(cu[k] <= a < cu[k + 1] and cu[k] <= b < cu[k + 1] for k in range(len(cu) - 1))
+    want_causal = np.array([[b <= a and same_doc(a, b) for b in pos] for a in pos])
+    want_full = np.array([[same_doc(a, b) for b in pos] for a in pos])
+    assert np.array_equal(orc.visible(pos, pos, cu), want_causal)
+    blk = dict(q_row0=0, n_q=20, k_row0=0, n_k=20, q_pos0=0, k_pos0=0, mask=orc.MASK_FULL)
+    assert np.array_equal(orc.block_visibility(blk, cu), want_full)
+    blk["mask"] = orc.MASK_CAUSAL_DIAG
+    assert np.array_equal(orc.block_visibility(blk, cu), want_causal)
+    assert orc.doc_of(pos, cu).tolist() == [-1] * 3 + [0] * 4 + [1] + [2] * 7 + [-1] * 5
+    rng = np.random.default_rng(8)
+    Q, K, V = _rand(rng, 20, 2, 4), _rand(rng, 20, 1, 4), _rand(rng, 20, 1, 4)
+    O, L = orc.causal_attention(Q, K, V, 0.5, cu_seqlens=np.array(cu))[:2]
+    outside = [0, 1, 2, 15, 16, 17, 18, 19]
+    assert np.all(O[outside] == 0) and np.all(np.isneginf(L[:, outside]))
+    assert np.all(np.isfinite(L[:, 3:15]))

@@ -438,3 +438,55 @@ def test_random_step_blocks(seed):
     blk = dict(q_row0=q_row0, n_q=n_q, k_row0=k_row0, n_k=n_k, mask=mask, q_pos0=q_pos0, k_pos0=k_pos0)
     _run_step(True, Hq, Hkv, 128, q_row0 + n_q + int(rng.integers(0, 9)), k_row0 + n_k + int(rng.integers(0, 9)), blk, cu=cu,
               seed=2000 + seed)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_ring_configurations(seed):
+    """Seeded random zigzag rings: ring size, chunk length (ragged against every tile size),
+    head grouping, one or two launch lanes, with or without packed documents (which may leave
+    positions outside every document), with or without host-side pruning of the sub-blocks."""
+    rng = np.random.default_rng(5000 + seed)
+    N = int(rng.integers(1, 5))
+    C = int(rng.choice([16, 33, 64, 96, 130, 200]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    Hq = Hkv * int(rng.choice([1, 2, 7]))
+    cfg = dict(dtype="bf16", Hq=Hq, Hkv=Hkv, d=128, N=N, C=C, sigma=0.5, seed=100 + seed)
+    prob = RankProblem(cfg)
+    T, n = prob.T, 2 * C
+    packed = rng.random() < 0.6
+    cu = None
+    if packed:
+        cuts = np.unique(rng.integers(0, T + 1, size=int(rng.integers(2, 7))))
+        cu = cuts.astype(np.int32) if len(cuts) >= 2 else np.array([0, T], dtype=np.int32)
+    K64, V64 = prob.K_full().astype(np.float64), prob.V_full().astype(np.float64)
+    dK_sum = np.zeros_like(K64); dV_sum = np.zeros_like(V64); dK_ref = np.zeros_like(K64); dV_ref = np.zeros_like(V64)
+    for r in range(N):
+        q, do = prob.rank_inputs(r)
+        _, l2g = orc.zigzag_layout(T, N, r)
+        ref = orc.causal_attention(q.astype(np.float64), K64, V64, prob.scale, cu_seqlens=cu, q_pos=l2g, dO=do.astype(np.float64))
+        if not packed:
+            out = prob.run_gpu(r, q, do, two_streams=bool(rng.integers(0, 2)))
+            o_acc, lse, dq, dk, dv = out["o_acc"], out["lse"], out["dq"], out["dk_zz"], out["dv_zz"]
+        else:
+            qd, dod = to_dev(q, True), to_dev(do, True)
+            cud = torch.from_numpy(cu).to(DEV)
+            shape = ring.shape_for(qd, prob.k_zz, B.MMSP_BF16, n, prob.scale)
+            o_acc = torch.empty(n, Hq, 128, dtype=torch.float32, device=DEV)
+            lse = torch.empty(Hq, n, dtype=torch.float32, device=DEV)
+            o_final = torch.empty_like(qd)
+            delta, dq = torch.empty_like(lse), torch.zeros_like(o_acc)
+            dk = torch.zeros(N, n, Hkv, 128, dtype=torch.float32, device=DEV)
+            dv = torch.zeros_like(dk)
+            ws_bytes = ring.workspace_bytes(shape, n, n)
+            ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+            cu_host = cu if rng.integers(0, 2) else None
+            ring.rank_forward_packed(shape, T, N, r, qd, prob.k_zz, prob.v_zz, cud, len(cu) - 1, o_acc, lse, o_final, ws=ws,
+                                     ws_bytes=ws_bytes, cu_host=cu_host)
+            ring.rank_backward_packed(shape, T, N, r, qd, prob.k_zz, prob.v_zz, cud, len(cu) - 1, o_final, dod, lse, delta, dq,
+                                      dk, dv, ws=ws, ws_bytes=ws_bytes, cu_host=cu_host)
+            torch.cuda.synchronize()
+        errs = dict(o=max_abs(to_host64(o_acc), ref[0]), lse=max_abs(to_host64(lse), ref[1]), dq=max_abs(to_host64(dq), ref[2]))
+        assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 and errs["dq"] <= 2e-2, (r, cfg, cu, errs)
+        dK_sum += prob.unzigzag(to_host64(dk)); dV_sum += prob.unzigzag(to_host64(dv))
+        dK_ref += ref[3]; dV_ref += ref[4]
+    assert max_abs(dK_sum, dK_ref) <= 2e-2 and max_abs(dV_sum, dV_ref) <= 2e-2, (cfg, cu)

@@ -141,15 +141,19 @@ def _run_step(io_bf16, Hq, Hkv, d, nq_tot, nk_tot, blk_kw, cu=None, seed=7, accu
     k0, k1 = ob["k_row0"], ob["k_row0"] + ob["n_k"]
     dqg, dkg, dvg = to_host64(dq), to_host64(dk), to_host64(dv)
     errs = (max_abs(dqg[r0:r1], dq_ref), max_abs(dkg[k0:k1], dk_ref), max_abs(dvg[k0:k1], dv_ref))
-    assert max(errs) <= tol["g"], errs
+    # fp32: 1e-5 is the bound for values of order one (the Tiny configuration); a gradient that sums hundreds of
+    # terms into values of order ten carries fp32 rounding in proportion, so the bound scales with the magnitude
+    mag = 1.0 if io_bf16 else max(1.0, float(np.abs(dq_ref).max(initial=0)), float(np.abs(dk_ref).max(initial=0)),
+                                  float(np.abs(dv_ref).max(initial=0)))
+    assert max(errs) <= tol["g"] * mag, errs
     assert np.all(dqg[:r0] == 0) and np.all(dqg[r1:] == 0)
     assert np.all(dkg[:k0] == sentinel) and np.all(dkg[k1:] == sentinel)
     assert np.all(dvg[:k0] == sentinel) and np.all(dvg[k1:] == sentinel)
     # accumulate_dkdv adds on top
     B.mmsp_attn_step_bwd(shape, blk, qd, kd, vd, None, dod, lse_full, delta, 0, dq, dk, dv, 1, ws, ws_bytes)
     torch.cuda.synchronize()
-    assert max_abs(to_host64(dk)[k0:k1], 2 * dk_ref) <= 2 * tol["g"]
-    assert max_abs(to_host64(dq)[r0:r1], 2 * dq_ref) <= 2 * tol["g"]
+    assert max_abs(to_host64(dk)[k0:k1], 2 * dk_ref) <= 2 * tol["g"] * mag
+    assert max_abs(to_host64(dq)[r0:r1], 2 * dq_ref) <= 2 * tol["g"] * mag
     return errs
 
 
@@ -416,7 +420,7 @@ def test_a2a_head_packing_bit_exact(t, U, hh, d):
 
 
 @pytest.mark.parametrize("seed", range(64))
-def test_random_step_blocks(seed):
+def test_random_step_blocks(seed, io_bf16=True, d=128):
     """Seeded random sub-blocks: sizes around the 32 / 64 / 128 / 256-row tile edges, random
     offsets into the tensors, positions that put the causal diagonal anywhere, optional random
     documents (some positions outside every document), random head grouping."""
@@ -436,8 +440,14 @@ def test_random_step_blocks(seed):
         if len(cu) < 2:
             cu = [0] + cu if cu[0] > 0 else cu + [hi]
     blk = dict(q_row0=q_row0, n_q=n_q, k_row0=k_row0, n_k=n_k, mask=mask, q_pos0=q_pos0, k_pos0=k_pos0)
-    _run_step(True, Hq, Hkv, 128, q_row0 + n_q + int(rng.integers(0, 9)), k_row0 + n_k + int(rng.integers(0, 9)), blk, cu=cu,
+    _run_step(io_bf16, Hq, Hkv, d, q_row0 + n_q + int(rng.integers(0, 9)), k_row0 + n_k + int(rng.integers(0, 9)), blk, cu=cu,
               seed=2000 + seed)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_step_blocks_fp32(seed):
+    """The same sweep through the fp32 kernels (head_dim 64 and 128, tolerance 1e-5)."""
+    test_random_step_blocks(400 + seed, io_bf16=False, d=64 if seed % 2 else 128)
 
 
 @pytest.mark.parametrize("seed", range(12))

@@ -242,13 +242,16 @@ def test_backward_is_bit_reproducible():
 
 
 def test_strided_q_and_kv_views():
-    """Q and K/V given as head-major views (explicit strides) give the same result as dense."""
+    """Q and K/V given as head-major views (explicit strides) give the same result as dense,
+    forward and backward (both backward kernels and their transposing pre-passes read Q, K, V
+    through the strides)."""
     rng = np.random.default_rng(50)
     n, Hq, Hkv, d = 200, 4, 2, 128
     q = synth.bf16_round(rng.standard_normal((n, Hq, d), dtype=np.float32) * 0.5)
     k = synth.bf16_round(rng.standard_normal((n, Hkv, d), dtype=np.float32) * 0.5)
     v = synth.bf16_round(rng.standard_normal((n, Hkv, d), dtype=np.float32) * 0.5)
-    qd, kd, vd = to_dev(q, True), to_dev(k, True), to_dev(v, True)
+    do = synth.bf16_round(rng.standard_normal((n, Hq, d), dtype=np.float32))
+    qd, kd, vd, dod = to_dev(q, True), to_dev(k, True), to_dev(v, True), to_dev(do, True)
     q_hm = qd.permute(1, 0, 2).contiguous().permute(1, 0, 2)       # [n,Hq,d] view of head-major storage
     k_hm = kd.permute(1, 0, 2).contiguous().permute(1, 0, 2)
     v_hm = vd.permute(1, 0, 2).contiguous().permute(1, 0, 2)
@@ -258,12 +261,22 @@ def test_strided_q_and_kv_views():
         shape = ring.shape_for(qq, kk, B.MMSP_BF16, n)
         o = torch.empty((n, Hq, d), dtype=torch.float32, device=DEV)
         lse = torch.empty((Hq, n), dtype=torch.float32, device=DEV)
+        of = torch.empty((n, Hq, d), dtype=torch.bfloat16, device=DEV)
+        delta, dq = torch.empty_like(lse), torch.zeros_like(o)
+        dk = torch.zeros((n, Hkv, d), dtype=torch.float32, device=DEV)
+        dv = torch.zeros_like(dk)
         ws_bytes = ring.workspace_bytes(shape, n, n)
         ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=DEV)
         B.mmsp_attn_step_fwd(shape, blk, qq, kk, vv, o, lse, 0, ws, ws_bytes)
+        B.mmsp_attn_merge(shape, 0, n, o, lse, None, None, of)
+        B.mmsp_attn_step_bwd(shape, blk, qq, kk, vv, of, dod, lse, delta, 1, dq, dk, dv, 0, ws, ws_bytes)
         torch.cuda.synchronize()
-        outs.append((o, lse))
-    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+        outs.append((o, lse, dq, dk, dv))
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a, b)
+    ref = orc.causal_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), 1 / math.sqrt(d), dO=do.astype(np.float64))
+    assert max_abs(to_host64(outs[1][2]), ref[2]) <= 2e-2 and max_abs(to_host64(outs[1][3]), ref[3]) <= 2e-2
+    assert max_abs(to_host64(outs[1][4]), ref[4]) <= 2e-2
 
 
 @pytest.mark.parametrize("U,R,Hq,Hkv", [(2, 2, 4, 2), (4, 2, 4, 2)])

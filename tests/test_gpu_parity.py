@@ -513,3 +513,44 @@ def test_random_ring_configurations(seed):
         dK_sum += prob.unzigzag(to_host64(dk)); dV_sum += prob.unzigzag(to_host64(dv))
         dK_ref += ref[3]; dV_ref += ref[4]
     assert max_abs(dK_sum, dK_ref) <= 2e-2 and max_abs(dV_sum, dV_ref) <= 2e-2, (cfg, cu)
+
+
+@pytest.mark.parametrize("sigma,ramp", [(2.0, 0.0), (1.0, 4.0), (3.0, 0.0)])
+def test_large_scores_exercise_the_lazy_rescale(sigma, ramp):
+    """Scores whose row maximum keeps growing along the keys (large sigma, or keys scaled up
+    with their position), so that the forward's lazy running-maximum update and O rescale run
+    many times and the softmax is nearly one-hot; forward and backward against the oracle."""
+    rng = np.random.default_rng(77)
+    n, Hq, Hkv, d = 700, 2, 1, 128
+    q = synth.bf16_round(rng.standard_normal((n, Hq, d), dtype=np.float32) * sigma)
+    k = rng.standard_normal((n, Hkv, d), dtype=np.float32) * sigma
+    k = synth.bf16_round(k * (1.0 + ramp * np.arange(n, dtype=np.float32)[:, None, None] / n))
+    v = synth.bf16_round(rng.standard_normal((n, Hkv, d), dtype=np.float32))
+    do = synth.bf16_round(rng.standard_normal((n, Hq, d), dtype=np.float32))
+    scale = 1 / math.sqrt(d)
+    ref = orc.causal_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), scale, dO=do.astype(np.float64))
+    qd, kd, vd, dod = to_dev(q, True), to_dev(k, True), to_dev(v, True), to_dev(do, True)
+    shape = ring.shape_for(qd, kd, B.MMSP_BF16, n, scale)
+    blk = B.make_block(0, n, 0, n, B.MMSP_MASK_CAUSAL_DIAG)
+    o = torch.empty((n, Hq, d), dtype=torch.float32, device=DEV)
+    lse = torch.empty((Hq, n), dtype=torch.float32, device=DEV)
+    of = torch.empty((n, Hq, d), dtype=torch.bfloat16, device=DEV)
+    delta, dq = torch.empty_like(lse), torch.zeros_like(o)
+    dk = torch.zeros((n, Hkv, d), dtype=torch.float32, device=DEV)
+    dv = torch.zeros_like(dk)
+    ws_bytes = ring.workspace_bytes(shape, n, n)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    B.mmsp_attn_step_fwd(shape, blk, qd, kd, vd, o, lse, 0, ws, ws_bytes)
+    B.mmsp_attn_merge(shape, 0, n, o, lse, None, None, of)
+    B.mmsp_attn_step_bwd(shape, blk, qd, kd, vd, of, dod, lse, delta, 1, dq, dk, dv, 0, ws, ws_bytes)
+    torch.cuda.synchronize()
+    assert float(np.abs(ref[1]).max()) > 10          # far above the lazy-update threshold (8 in the exponent of 2)
+    # LSE values of order 100 carry fp32 rounding of order 1e-5 * 100; O and the gradients keep the bf16 bound,
+    # scaled by the magnitude of the values they are built from where that exceeds one
+    errs = dict(o=max_abs(to_host64(o), ref[0]), lse=max_abs(to_host64(lse), ref[1]), dq=max_abs(to_host64(dq), ref[2]),
+                dk=max_abs(to_host64(dk), ref[3]), dv=max_abs(to_host64(dv), ref[4]))
+    mags = dict(o=1.0, lse=1.0, dq=max(1.0, np.abs(ref[2]).max()), dk=max(1.0, np.abs(ref[3]).max()), dv=max(1.0, np.abs(ref[4]).max()))
+    print("large-score errors", errs, "magnitudes", mags, flush=True)
+    assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 * max(1.0, np.abs(ref[1]).max() / 10)
+    for g in ("dq", "dk", "dv"):
+        assert errs[g] <= 2e-2 * mags[g], (g, errs, mags)

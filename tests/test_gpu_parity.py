@@ -515,7 +515,7 @@ def test_random_ring_configurations(seed):
     assert max_abs(dK_sum, dK_ref) <= 2e-2 and max_abs(dV_sum, dV_ref) <= 2e-2, (cfg, cu)
 
 
-@pytest.mark.parametrize("sigma,ramp", [(2.0, 0.0), (1.0, 4.0), (3.0, 0.0)])
+@pytest.mark.parametrize("sigma,ramp", [(2.0, 0.0), (1.0, 4.0), (3.0, 0.0), (8.0, 0.0)])
 def test_large_scores_exercise_the_lazy_rescale(sigma, ramp):
     """Scores whose row maximum keeps growing along the keys (large sigma, or keys scaled up
     with their position), so that the forward's lazy running-maximum update and O rescale run

@@ -554,3 +554,21 @@ def test_large_scores_exercise_the_lazy_rescale(sigma, ramp):
     assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 * max(1.0, np.abs(ref[1]).max() / 10)
     for g in ("dq", "dk", "dv"):
         assert errs[g] <= 2e-2 * mags[g], (g, errs, mags)
+
+
+@pytest.mark.parametrize("io_bf16", [True, False])
+def test_many_tiny_documents(io_bf16):
+    """Hundreds of documents of 1 to 5 tokens (every tile cuts many document boundaries), and a
+    one-token-per-document pack, where every row sees exactly itself (P = 1, O = V, LSE = s_ii)."""
+    rng = np.random.default_rng(91)
+    n = 600
+    lens = rng.integers(1, 6, size=400)
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    cu = cu[cu <= n].tolist()
+    if cu[-1] != n:
+        cu.append(n)
+    d = 128 if io_bf16 else 64
+    for mask in (B.MMSP_MASK_CAUSAL_DIAG, B.MMSP_MASK_FULL):
+        _run_step(io_bf16, 4, 2, d, n, n, dict(q_row0=0, n_q=n, k_row0=0, n_k=n, mask=mask), cu=cu, seed=92)
+    _run_step(io_bf16, 2, 1, d, 300, 300, dict(q_row0=0, n_q=300, k_row0=0, n_k=300, mask=B.MMSP_MASK_CAUSAL_DIAG),
+              cu=list(range(301)), seed=93)

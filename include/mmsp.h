@@ -86,8 +86,8 @@ typedef struct {
                                 on belong to no document and see nothing.                  */
 } mmsp_block;
 
-/* Zigzag ("both ends") sharding -- Sec. 4.2 "MM-SP workflow": the sequence is cut into 2N
- * equal chunks and rank r takes chunk r and chunk 2N-1-r, so every rank owns the same
+/* Zigzag sharding (chunks dealt from the two ends of the sequence) -- Sec. 4.2, MM-SP
+ * workflow: the sequence is cut into 2N equal chunks and rank r takes chunk r and chunk 2N-1-r, so every rank owns the same
  * number of causal pairs.  chunk_ids (host, 2 ints) receives {r, 2N-1-r}.
  * local_to_global (host, T/N int64, may be NULL) receives the global token index of each
  * local row (ascending).  INVALID_ARG if T <= 0, N <= 0, T % (2N) != 0 or rank not in [0,N). */
@@ -114,7 +114,7 @@ mmsp_status mmsp_contiguous_plan(int64_t T, int32_t N, int32_t rank, int32_t ste
                                  int32_t* src_rank, mmsp_block* blk);
 
 /* The same ring step for a packed (variable-length) sequence whose document mask is given by
- * cu_seqlens on global positions -- Sec. 4.2 "MM-SP workflow" (token-level sharding of the
+ * cu_seqlens on global positions -- Sec. 4.2, MM-SP workflow (token-level sharding of the
  * packed vision + text inputs from both ends).  A rank's local rows are two segments with
  * different global positions, and so is the visiting block, so the step is cut into
  * sub-blocks of one query segment x one key segment, inside which positions are consecutive:
@@ -153,7 +153,7 @@ typedef struct {
 mmsp_status mmsp_2d_layout(int64_t T, int32_t U, int32_t R, int32_t gpu, int32_t n_q_heads, int32_t n_kv_heads,
                            mmsp_2d_share* share);
 
-/* Token-level sharding of a whole sequence "from both ends" -- Sec. 4.2 "MM-SP workflow" (the
+/* Token-level zigzag sharding of a whole sequence -- Sec. 4.2, MM-SP workflow (the
  * second stage of the two-stage sharding).  seq (device) holds T rows of row_bytes bytes in
  * sequence order (a row is one token's heads x d elements, any dtype); shards (device) holds
  * the N ranks' local rows back to back, [N][2C] rows with C = T / (2N), rank r = chunk r then
@@ -184,8 +184,8 @@ mmsp_status mmsp_a2a_unpack_heads(int64_t n_tokens, int32_t U, int64_t slice_byt
  * streams) need separate workspaces. */
 size_t mmsp_workspace_bytes(const mmsp_shape* shape, int64_t n_q_max, int64_t n_k_max, int backward);
 
-/* One ring step, forward (the "local attention computation within each SP group rank" of
- * the comparison figure):  for each query head h and query row i of the block,
+/* One ring step, forward (the per-rank attention of one ring round; comparison figure,
+ * Sec. 4.2):  for each query head h and query row i of the block,
  *   S_j = softmax_scale * Q[i,h,:] . K[j,kv(h),:]  over the visible keys j of the block,
  *   LSE_part = ln sum_j exp(S_j),  O_part = sum_j exp(S_j - LSE_part) V[j,kv(h),:].
  * accumulate == 0: o and lse are overwritten with (O_part, LSE_part) for rows of the block.

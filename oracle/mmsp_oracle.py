@@ -23,7 +23,8 @@ Conventions that the paper leaves open are the readings listed in the design doc:
 
 All arrays are numpy float64.  Shapes: Q [nq, Hq, d], K/V [nk, Hkv, d], O like Q,
 LSE [Hq, nq].  Positions are integer arrays giving each row's index in the full packed
-sequence; `cu_seqlens` (ascending, [0]=0, last = total length) delimits documents.
+sequence; `cu_seqlens` (ascending, [n_docs + 1]) delimits documents [cu[k], cu[k+1]); a
+position below cu[0] or from cu[n_docs] on belongs to no document and sees nothing.
 """
 import numpy as np
 

@@ -64,8 +64,9 @@ mmsp_status check_block(const mmsp_shape* s, const mmsp_block* b) {
   if (b->k_row0 < 0 || b->n_k < 0 || b->k_row0 + b->n_k > kMaxExtent)
     return fail(MMSP_ERR_INVALID_ARG, "key range [%lld, +%lld) is negative or exceeds 2^30", (long long)b->k_row0,
                 (long long)b->n_k);
-  if (b->q_pos0 < -kMaxExtent || b->q_pos0 > kMaxExtent || b->k_pos0 < -kMaxExtent || b->k_pos0 > kMaxExtent)
-    return fail(MMSP_ERR_INVALID_ARG, "q_pos0 / k_pos0 exceed 2^30 in magnitude");
+  // positions are int32 inside the kernels: the last position of either side must fit too
+  if (b->q_pos0 < -kMaxExtent || b->q_pos0 + b->n_q > kMaxExtent || b->k_pos0 < -kMaxExtent || b->k_pos0 + b->n_k > kMaxExtent)
+    return fail(MMSP_ERR_INVALID_ARG, "positions [q_pos0, q_pos0 + n_q) and [k_pos0, k_pos0 + n_k) must lie in [-2^30, 2^30]");
   if (b->mask != MMSP_MASK_FULL && b->mask != MMSP_MASK_CAUSAL_DIAG && b->mask != MMSP_MASK_NONE)
     return fail(MMSP_ERR_INVALID_ARG, "mask=%d is not a mmsp_mask", b->mask);
   if ((b->cu_seqlens == nullptr) != (b->n_docs == 0) || b->n_docs < 0)
@@ -356,6 +357,12 @@ mmsp_status mmsp_attn_step_bwd(const mmsp_shape* shape, const mmsp_block* blk, c
       !aligned16(dq_acc) || !aligned16(dk) || !aligned16(dv))
     return fail(MMSP_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  // every check comes before the first launch: a failing call enqueues nothing
+  const bool has_pairs = blk->n_k > 0 && blk->n_q > 0 && blk->mask != MMSP_MASK_NONE;
+  if (has_pairs) {
+    st = check_workspace(shape, blk, true, workspace, workspace_bytes);
+    if (st != MMSP_OK) return st;
+  }
   if (compute_delta && blk->n_q > 0) {
     hipError_t e = mmsp::launch_delta(o_final, d_o, delta, shape->io_dtype, shape->lse_head_stride, shape->n_q_heads,
                                       shape->head_dim, (int)blk->q_row0, (int)blk->n_q, stream);
@@ -370,8 +377,6 @@ mmsp_status mmsp_attn_step_bwd(const mmsp_shape* shape, const mmsp_block* blk, c
     if (e == hipSuccess) e = mmsp::launch_zero_f32(dv + first, count, stream);
     return device_result(e, "zero dk/dv");
   }
-  st = check_workspace(shape, blk, true, workspace, workspace_bytes);
-  if (st != MMSP_OK) return st;
   mmsp::StepArgs a = make_args(shape, blk);
   a.ws = reinterpret_cast<char*>(workspace);
   a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.lse_final = lse_final; a.delta = delta;

@@ -63,24 +63,23 @@ class RankProblem:
         qd = to_dev(q, self.bf16)
         io = B.MMSP_BF16 if self.bf16 else B.MMSP_F32
         shape = ring.shape_for(qd, self.k_zz, io, n, self.scale)
-        o_acc = torch.empty(n, self.Hq, self.d, dtype=torch.float32, device=DEV)
-        lse = torch.empty(self.Hq, n, dtype=torch.float32, device=DEV)
-        o_final = torch.empty_like(qd)
+        o_acc = nans(n, self.Hq, self.d)
+        lse = nans(self.Hq, n)
+        o_final = nans_like(qd)
         o_part = lse_part = None
         if not fused_merge:
-            o_part, lse_part = torch.empty_like(o_acc), torch.empty_like(lse)
+            o_part, lse_part = nans_like(o_acc), nans_like(lse)
         ws_bytes = ring.workspace_bytes(shape, n, n)
         ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=DEV)
         side = None
         if two_streams:
-            side = ring.SideLane(torch.cuda.Stream(), torch.empty_like(o_acc), torch.empty_like(lse),
-                                 torch.empty_like(ws), ws_bytes)
+            side = ring.SideLane(torch.cuda.Stream(), nans_like(o_acc), nans_like(lse), torch.empty_like(ws), ws_bytes)
         ring.rank_forward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, o_acc, lse, o_final,
                           fused_merge=fused_merge, o_part=o_part, lse_part=lse_part, ws=ws, ws_bytes=ws_bytes, side=side)
         out = dict(o_acc=o_acc, lse=lse, o_final=o_final)
         if do is not None:
             dod = to_dev(do, self.bf16)
-            delta = torch.empty_like(lse)
+            delta = nans_like(lse)
             dq = torch.zeros_like(o_acc)
             dk = torch.zeros(self.N, n, self.Hkv, self.d, dtype=torch.float32, device=DEV)
             dv = torch.zeros_like(dk)
@@ -101,12 +100,30 @@ class RankProblem:
 
 
 def max_abs(a, b):
+    """Largest |a - b|.  Infinities of the same sign in the same place count as equal (LSE of a row
+    that sees nothing is -inf on both sides); a NaN on either side, or an infinity facing anything
+    else, makes the result inf so that every `max_abs(...) <= tol` assertion fails on it."""
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
+    if a.shape != b.shape:
+        raise ValueError("max_abs: shapes %s and %s differ" % (a.shape, b.shape))
+    if not a.size:
+        return 0.0
+    if np.isnan(a).any() or np.isnan(b).any():
+        return float("inf")
     both_inf = np.isinf(a) & np.isinf(b) & (np.sign(a) == np.sign(b))
     with np.errstate(invalid="ignore"):          # inf - inf of matching infinities, replaced just below
         diff = np.where(both_inf, 0.0, np.abs(a - b))
-    return float(np.nanmax(diff)) if diff.size else 0.0
+    return float(np.max(diff))
+
+
+def nans(*shape, dtype=torch.float32):
+    """Output buffer pre-filled with NaN: a row the kernels fail to write then fails the comparison."""
+    return torch.full(shape, float("nan"), dtype=dtype, device=DEV)
+
+
+def nans_like(t):
+    return torch.full_like(t, float("nan"))
 
 
 def oracle_rows(prob, q_rows, q_pos, do_rows=None, heads=None, cu=None):

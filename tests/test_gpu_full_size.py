@@ -12,7 +12,7 @@ import torch
 from oracle import mmsp_oracle as orc
 from paper_2408_10188_amd import binding as B
 from paper_2408_10188_amd import ring, synth
-from tests.helpers import DEV, RankProblem, max_abs, to_dev, to_host64
+from tests.helpers import DEV, RankProblem, max_abs, nans, nans_like, to_dev, to_host64
 
 pytestmark = pytest.mark.gpu
 
@@ -107,10 +107,10 @@ def test_ulysses_packed_fwd_bwd_sampled_rows():
     qd, kd, vd, dod = (to_dev(x, True) for x in (q, k, v, do))
     cud = torch.from_numpy(cu).to(DEV)
     shape = ring.shape_for(qd, kd, B.MMSP_BF16, T, scale)
-    o_acc = torch.empty(T, Hq, d, dtype=torch.float32, device=DEV)
-    lse = torch.empty(Hq, T, dtype=torch.float32, device=DEV)
-    o_final = torch.empty_like(qd)
-    delta = torch.empty_like(lse)
+    o_acc = nans(T, Hq, d)
+    lse = nans(Hq, T)
+    o_final = nans_like(qd)
+    delta = nans_like(lse)
     dq = torch.zeros_like(o_acc)
     dk = torch.zeros(T, Hkv, d, dtype=torch.float32, device=DEV)
     dv = torch.zeros_like(dk)

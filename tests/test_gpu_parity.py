@@ -11,7 +11,7 @@ import torch
 from oracle import mmsp_oracle as orc
 from paper_2408_10188_amd import binding as B
 from paper_2408_10188_amd import ring, synth
-from tests.helpers import DEV, RankProblem, max_abs, to_dev, to_host64
+from tests.helpers import DEV, RankProblem, max_abs, nans, nans_like, to_dev, to_host64
 
 pytestmark = pytest.mark.gpu
 
@@ -259,10 +259,10 @@ def test_strided_q_and_kv_views():
     outs = []
     for qq, kk, vv in ((qd, kd, vd), (q_hm, k_hm, v_hm)):
         shape = ring.shape_for(qq, kk, B.MMSP_BF16, n)
-        o = torch.empty((n, Hq, d), dtype=torch.float32, device=DEV)
-        lse = torch.empty((Hq, n), dtype=torch.float32, device=DEV)
-        of = torch.empty((n, Hq, d), dtype=torch.bfloat16, device=DEV)
-        delta, dq = torch.empty_like(lse), torch.zeros_like(o)
+        o = nans(n, Hq, d)
+        lse = nans(Hq, n)
+        of = nans(n, Hq, d, dtype=torch.bfloat16)
+        delta, dq = nans_like(lse), torch.zeros_like(o)
         dk = torch.zeros((n, Hkv, d), dtype=torch.float32, device=DEV)
         dv = torch.zeros_like(dk)
         ws_bytes = ring.workspace_bytes(shape, n, n)
@@ -304,10 +304,10 @@ def test_two_d_attention_shares(U, R, Hq, Hkv):
         k_zz, v_zz = prob.k_zz[:, :, kv0:kv0 + nkv], prob.v_zz[:, :, kv0:kv0 + nkv]
         dod = to_dev(do, True)[:, h0:h0 + nh].contiguous()
         shape = ring.shape_for(qd, k_zz, B.MMSP_BF16, n, prob.scale)
-        o_acc = torch.empty(n, nh, d, dtype=torch.float32, device=DEV)
-        lse = torch.empty(nh, n, dtype=torch.float32, device=DEV)
-        o_final = torch.empty(n, nh, d, dtype=torch.bfloat16, device=DEV)
-        delta, dq = torch.empty_like(lse), torch.zeros_like(o_acc)
+        o_acc = nans(n, nh, d)
+        lse = nans(nh, n)
+        o_final = nans(n, nh, d, dtype=torch.bfloat16)
+        delta, dq = nans_like(lse), torch.zeros_like(o_acc)
         dk = torch.zeros(R, n, nkv, d, dtype=torch.float32, device=DEV)
         dv = torch.zeros_like(dk)
         ws_bytes = ring.workspace_bytes(shape, n, n)
@@ -348,10 +348,10 @@ def test_zigzag_ring_over_packed_documents(dtype, N, C, d, cuts):
         ref = orc.causal_attention(q.astype(np.float64), K64, V64, prob.scale, cu_seqlens=cu, q_pos=l2g, dO=do.astype(np.float64))
         qd, dod = to_dev(q, bf16), to_dev(do, bf16)
         shape = ring.shape_for(qd, prob.k_zz, B.MMSP_BF16 if bf16 else B.MMSP_F32, n, prob.scale)
-        o_acc = torch.empty(n, prob.Hq, d, dtype=torch.float32, device=DEV)
-        lse = torch.empty(prob.Hq, n, dtype=torch.float32, device=DEV)
-        o_final = torch.empty_like(qd)
-        delta, dq = torch.empty_like(lse), torch.zeros_like(o_acc)
+        o_acc = nans(n, prob.Hq, d)
+        lse = nans(prob.Hq, n)
+        o_final = nans_like(qd)
+        delta, dq = nans_like(lse), torch.zeros_like(o_acc)
         dk = torch.zeros(N, n, prob.Hkv, d, dtype=torch.float32, device=DEV)
         dv = torch.zeros_like(dk)
         ws_bytes = ring.workspace_bytes(shape, n, n)
@@ -386,10 +386,10 @@ def test_contiguous_ring_layout():
         rows = slice(r * L, (r + 1) * L)
         qd, dod = to_dev(Q[rows], True), to_dev(dO[rows], True)
         shape = ring.shape_for(qd, k_blk, B.MMSP_BF16, L, scale)
-        o_acc = torch.empty(L, Hq, d, dtype=torch.float32, device=DEV)
-        lse = torch.empty(Hq, L, dtype=torch.float32, device=DEV)
-        o_final = torch.empty_like(qd)
-        delta, dq = torch.empty_like(lse), torch.zeros_like(o_acc)
+        o_acc = nans(L, Hq, d)
+        lse = nans(Hq, L)
+        o_final = nans_like(qd)
+        delta, dq = nans_like(lse), torch.zeros_like(o_acc)
         dk = torch.zeros(N, L, Hkv, d, dtype=torch.float32, device=DEV)
         dv = torch.zeros_like(dk)
         ws_bytes = ring.workspace_bytes(shape, L, L)
@@ -422,7 +422,7 @@ def test_zigzag_gather_scatter_bit_exact(T, N, H, d, dtype):
 @pytest.mark.parametrize("t,U,hh,d", [(5, 4, 2, 8), (1000, 4, 7, 128), (333, 7, 1, 128)])
 def test_a2a_head_packing_bit_exact(t, U, hh, d):
     x = torch.randn(t, U * hh, d, device=DEV).bfloat16()
-    y = torch.empty(U, t, hh, d, dtype=torch.bfloat16, device=DEV)
+    y = nans(U, t, hh, d, dtype=torch.bfloat16)
     B.mmsp_a2a_pack_heads(t, U, hh * d * 2, x, y)
     back = torch.empty_like(x)
     B.mmsp_a2a_unpack_heads(t, U, hh * d * 2, y, back)
@@ -494,10 +494,10 @@ def test_random_ring_configurations(seed):
             qd, dod = to_dev(q, True), to_dev(do, True)
             cud = torch.from_numpy(cu).to(DEV)
             shape = ring.shape_for(qd, prob.k_zz, B.MMSP_BF16, n, prob.scale)
-            o_acc = torch.empty(n, Hq, 128, dtype=torch.float32, device=DEV)
-            lse = torch.empty(Hq, n, dtype=torch.float32, device=DEV)
-            o_final = torch.empty_like(qd)
-            delta, dq = torch.empty_like(lse), torch.zeros_like(o_acc)
+            o_acc = nans(n, Hq, 128)
+            lse = nans(Hq, n)
+            o_final = nans_like(qd)
+            delta, dq = nans_like(lse), torch.zeros_like(o_acc)
             dk = torch.zeros(N, n, Hkv, 128, dtype=torch.float32, device=DEV)
             dv = torch.zeros_like(dk)
             ws_bytes = ring.workspace_bytes(shape, n, n)
@@ -532,10 +532,10 @@ def test_large_scores_exercise_the_lazy_rescale(sigma, ramp):
     qd, kd, vd, dod = to_dev(q, True), to_dev(k, True), to_dev(v, True), to_dev(do, True)
     shape = ring.shape_for(qd, kd, B.MMSP_BF16, n, scale)
     blk = B.make_block(0, n, 0, n, B.MMSP_MASK_CAUSAL_DIAG)
-    o = torch.empty((n, Hq, d), dtype=torch.float32, device=DEV)
-    lse = torch.empty((Hq, n), dtype=torch.float32, device=DEV)
-    of = torch.empty((n, Hq, d), dtype=torch.bfloat16, device=DEV)
-    delta, dq = torch.empty_like(lse), torch.zeros_like(o)
+    o = nans(n, Hq, d)
+    lse = nans(Hq, n)
+    of = nans(n, Hq, d, dtype=torch.bfloat16)
+    delta, dq = nans_like(lse), torch.zeros_like(o)
     dk = torch.zeros((n, Hkv, d), dtype=torch.float32, device=DEV)
     dv = torch.zeros_like(dk)
     ws_bytes = ring.workspace_bytes(shape, n, n)

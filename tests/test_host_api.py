@@ -149,6 +149,8 @@ FAKE = 0x1000  # a 16-byte aligned non-NULL value; never dereferenced because va
     ({}, dict(mask=5), B.MMSP_ERR_INVALID_ARG),
     ({}, dict(n_docs=3), B.MMSP_ERR_INVALID_ARG),                   # n_docs without cu_seqlens
     ({}, dict(q_pos0=1 << 40), B.MMSP_ERR_INVALID_ARG),
+    ({}, dict(q_pos0=(1 << 30) - 8), B.MMSP_ERR_INVALID_ARG),       # q_pos0 + n_q leaves the int32-safe range
+    ({}, dict(k_pos0=(1 << 30) - 15), B.MMSP_ERR_INVALID_ARG),      # k_pos0 + n_k likewise
 ])
 def test_step_calls_reject_bad_shapes_and_blocks(shape_kw, blk_kw, status):
     shape = _shape(**shape_kw)
@@ -197,6 +199,17 @@ def test_workspace_size_and_rejection():
     with pytest.raises(B.MmspError) as e:
         B.mmsp_attn_step_fwd(shape, blk, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 100)
     assert e.value.status == B.MMSP_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_backward_checks_the_workspace_before_it_launches_anything():
+    """compute_delta with a short workspace: the call must fail on the workspace, not after the
+    delta kernel has been enqueued.  Without a GPU a launch would come back as MMSP_ERR_DEVICE,
+    so the status also shows that no launch was attempted."""
+    shape, blk = _shape(), B.make_block(0, 16, 0, 16, B.MMSP_MASK_FULL)
+    for ws, nbytes in ((None, 0), (FAKE, 64)):
+        with pytest.raises(B.MmspError) as e:
+            B.mmsp_attn_step_bwd(shape, blk, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, FAKE, FAKE, FAKE, 0, ws, nbytes)
+        assert e.value.status == B.MMSP_ERR_WORKSPACE_TOO_SMALL
 
 
 def test_data_movement_calls_reject_bad_arguments():

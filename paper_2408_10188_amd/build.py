@@ -6,8 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmmsp.so")
-PROBE = os.path.join(HERE, "ceiling_probe")
-SOURCES = ["api.hip", "elementwise.hip", "layout.hip", "ref_f32.hip", "transpose.hip", "fwd_bf16.hip", "bwd_bf16.hip", "bwd_dq_bf16.hip", "bwd_dkdv_bf16.hip"]
+SOURCES = ["api.hip", "elementwise.hip", "layout.hip", "ref_f32.hip", "fwd_bf16.hip", "bwd_bf16.hip", "bwd_dq_bf16.hip", "bwd_dkdv_bf16.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 EXTRA = os.environ.get("MMSP_EXTRA", "").split()
 FLAGS = [*EXTRA, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
@@ -34,11 +33,6 @@ def build_library(verbose=False, jobs=5):
     out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if out.returncode != 0:
         raise RuntimeError("link failed:\n" + out.stdout)
-    # stand-alone measurement program (bench.py --ceiling), not part of the library
-    cmd = [HIPCC, *FLAGS, "-Wno-unused-value", os.path.join(CSRC, "ceiling_probe.hip"), "-o", PROBE]
-    out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if out.returncode != 0:
-        raise RuntimeError("ceiling_probe build failed:\n" + out.stdout)
     return LIB
 
 

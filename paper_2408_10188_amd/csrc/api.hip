@@ -91,12 +91,12 @@ mmsp_status device_result(hipError_t e, const char* what) {
   return fail(MMSP_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
 }
 
-// bf16 kernels read token-contiguous operands from pre-transposed tile images (16 KiB per 64
-// rows and head) that each call builds in the workspace: V^T for the forward; Q^T, dO^T and the
-// padded row statistics (dK/dV kernel) plus K^T (dQ kernel) for the backward.
+// Only the bf16 backward needs scratch: padded row statistics and the partial dK / dV sums of
+// split key tiles (dK/dV kernel).
 size_t needed_workspace(const mmsp_shape* s, int64_t n_q, int64_t n_k, bool backward) {
-  if (backward) return (size_t)mmsp::bwd_bf16_total_workspace_bytes(s->n_q_heads, s->n_kv_heads, n_q, n_k);
-  return (size_t)(s->n_kv_heads * mmsp::tiles_of(n_k) * mmsp::kImageBytes);
+  (void)n_k;
+  if (backward) return (size_t)mmsp::bwd_bf16_workspace_bytes(s->n_q_heads, n_q);
+  return 0;
 }
 
 mmsp_status check_workspace(const mmsp_shape* s, const mmsp_block* b, bool backward, const void* ws, size_t ws_bytes) {

@@ -1,19 +1,24 @@
 // Backward ring step, dK/dV kernel (key-stationary) on bf16 matrix cores, head_dim 128.
 //
-// Workgroup = 8 wavefronts = 128 keys of one KV head.  The wavefronts are specialised in pairs
-// that share 32 keys and, with the round-robin wavefront placement, a SIMD:
-//   "P" wavefront (0..3):  S = Q K^T,  P = exp2(S*c - LSE*log2e),  dV^T += dO^T P
-//   "D" wavefront (4..7):  dP = dO V^T,  dS = P * (dP - delta),    dK^T += Q^T dS
-// P travels from the first to the second through LDS, already packed as an MFMA B operand (the
-// two wavefronts use the same lane <-> (key, query) mapping, so it is a straight copy).  Each
-// wavefront keeps one 128 d x 32 key accumulator and one of K / V in registers, which fits the
-// plain VGPR file with two wavefronts per SIMD, and the two of a pair do the same number of
-// MFMAs, so one's exp / dS arithmetic overlaps the other's matrix work.
+// Workgroup = 4 wavefronts (one per SIMD, the whole 512-entry register file each) = 128 keys of
+// one KV head.  A wavefront owns 32 keys and keeps their K and V rows (MFMA B operands) and the
+// two accumulators dK^T, dV^T (128 d x 32 keys each) in registers for the whole call.  64-row
+// tiles of Q and dO of every query head of the group stream through a four-slot LDS ring filled
+// by asynchronous global->LDS copies straight from the caller's tensors (natural orientation;
+// the second products read them back transposed with ds_read_b64_tr_b16), the per-row
+// statistics (-LSE*log2e, delta) from padded copies in the workspace.  Per 32-row block:
+//   S = Q K^T,  dP = dO V^T            (A = Q / dO rows from LDS, B = K / V registers)
+//   P = exp2(S*c - LSE*log2e),  dS = P * (dP - delta)
+//   dV^T += dO^T P,  dK^T += Q^T dS    (A = dO / Q read transposed, B = P / dS straight from registers)
+// Nothing passes between wavefronts, so the only workgroup barrier is the one that hands a ring
+// slot over, once per tile.
 //
-// 64-row tiles of Q and dO of every query head of the group stream through a two-stage LDS
-// ring filled by asynchronous global->LDS copies: the natural tiles straight from the caller's
-// tensors, the transposed ones (Q^T, dO^T) from tile images pre-built in the workspace, the
-// per-row statistics (-LSE*log2e, delta) from padded copies there.
+// A matrix instruction keeps the SIMD's matrix pipe busy for 32 cycles but its issue port for
+// about 8, so a wavefront keeps the pipe full on its own if independent vector and LDS
+// instructions are interleaved with the matrix instructions in program order.  The loop is
+// software-pipelined over blocks: while the pipe computes S and dP of block b+1 the vector units
+// turn dP of block b into dS; while it accumulates dV and dK of block b they take the exponentials
+// of block b+1.  The operand of every matrix instruction is read from LDS four instructions ahead.
 #include "mfma_tiles.h"
 
 namespace mmsp {
@@ -21,14 +26,20 @@ namespace {
 
 constexpr int kKeys = 128;          // keys per workgroup
 constexpr int kBQ = 64;             // query rows per streamed tile
-constexpr int kWaves = 8;
-constexpr int kCopies = 16 / kWaves;
-constexpr int kStage = 4 * kTileBytes;   // Q TileN | dO TileN | Q^T TileT | dO^T TileT
+constexpr int kWaves = 4;
+constexpr int kCopies = 16 / kWaves;            // 1 KiB copies per wavefront and 16 KiB tile
+constexpr int kGroup = 2 * kCopies + 1;         // copies per wavefront and ring slot: Q, dO, one statistics row
+constexpr int kSlots = 4;
+constexpr int kDepth = 4;                        // LDS operand reads in flight ahead of the matrix instructions (power of two)
 
 __device__ __forceinline__ void dma4(const char* gptr, char* lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 4, 0, 0);
 }
+
+#define MMSP_PIN(x) asm volatile("" : "+v"(x))
+#define MMSP_PIN_ACC(x) asm volatile("" : "+a"(x))     // keeps an accumulator in the AGPR half of the register file
+#define MMSP_STEP_END() __builtin_amdgcn_sched_barrier(0)
 
 // kMask = false: the host has checked that every (query, key) pair of the block is visible and
 // that n_q is a multiple of the tile length, so no tile needs masking.
@@ -36,18 +47,25 @@ __device__ __forceinline__ void dma4(const char* gptr, char* lds_wave_base) {
 // workgroups, which store their partial dK / dV into w.partial for dkdv_reduce_kernel to sum
 // (used when one workgroup per key tile would leave CUs idle or unevenly loaded).
 template <bool kMask>
-__global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWorkspace w, int n_kt, int xcd_per_kv,
+__global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWorkspace w, int n_kt, int xcd_per_kv,
                                                                        int nsplit) {
-  __shared__ __attribute__((aligned(1024))) char stage0[kStage];
-  __shared__ __attribute__((aligned(1024))) char stage1[kStage];
-  __shared__ __attribute__((aligned(1024))) float stat0[128];      // [0,64) -LSE*log2e, [64,128) delta
-  __shared__ __attribute__((aligned(1024))) float stat1[128];
-  __shared__ __attribute__((aligned(1024))) char pxch[2 * 4 * 2048];   // P of a block: [slot][pair][half of the lane's 32 B][lane * 16 B]
+  // One array per ring slot, selected at compile time, so that the compiler can tell the reads of
+  // one slot from the copies in flight into another.
+  __shared__ __attribute__((aligned(1024))) char qs0[kTileBytes];    // Q tiles, TileS
+  __shared__ __attribute__((aligned(1024))) char qs1[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char qs2[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char qs3[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char os0[kTileBytes];    // dO tiles, TileS
+  __shared__ __attribute__((aligned(1024))) char os1[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char os2[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char os3[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) float st0[128];          // [0,64) -LSE*log2e, [64,128) delta
+  __shared__ __attribute__((aligned(1024))) float st1[128];
+  __shared__ __attribute__((aligned(1024))) float st2[128];
+  __shared__ __attribute__((aligned(1024))) float st3[128];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, col = lane & 31;
-  const int pair = wave & 3;                    // which 32 keys
-  const bool role_p = wave < 4;                 // true: S / P / dV,  false: dP / dS / dK
 
   int kvh, item;                    // item = key tile * nsplit + range
   if (xcd_per_kv > 0) {             // workgroups of one KV head share an XCD (its L2 then serves the Q/dO stream once)
@@ -61,7 +79,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   }
   const int kt = item / nsplit, split = item % nsplit;
   const int tile_key0 = kt * kKeys;
-  const int key = tile_key0 + pair * 32 + col;           // block-relative key of this lane
+  const int key = tile_key0 + wave * 32 + col;           // block-relative key of this lane
   const bool live = key < a.n_k;
   const int keyc = min(key, a.n_k - 1);
 
@@ -73,7 +91,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   row_interval_of_key(a, min(tile_key0 + kKeys, a.n_k) - 1, dummy, t_hi);
   int w_lo_max, w_hi_min;
   {
-    const int wk0 = min(tile_key0 + pair * 32, a.n_k - 1);
+    const int wk0 = min(tile_key0 + wave * 32, a.n_k - 1);
     row_interval_of_key(a, wk0, dummy, w_hi_min);
     w_lo_max = __shfl(rlo, 31);                          // last key of the wavefront (n_q for a dead key: always mask)
   }
@@ -87,270 +105,315 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dkdv_bf16_kernel(StepArgs 
   // this workgroup's share of the (query tile, head of the group) sequence: elements split,
   // split + nsplit, ...  (interleaved rather than contiguous, so that the workgroups of a key
   // tile, and of neighbouring key tiles, walk the Q / dO tiles at the same place and pace and
-  // share them in L2)
-  int it0 = split, niter = 0;
+  // share them in L2).  Sequence order: query tiles from the last visible one downwards, the
+  // heads of the group inside a tile: under a causal or document mask the key tiles that share
+  // an XCD see query ranges with different starts but a common end.
+  int niter = 0;
   if (ntiles > 0) {
     const int total = ntiles * a.group;
     niter = total > split ? (total - split + nsplit - 1) / nsplit : 0;
   }
-  // Sequence order: query tiles from the last visible one downwards, the heads of the group
-  // inside a tile.  Under a causal or document mask the key tiles that share an XCD see query
-  // ranges with different starts but a common end, so walking down from the end keeps their
-  // workgroups on the same Q / dO tiles (served once from HBM, then from L2) for as long as
-  // their ranges overlap.
-  const int hg_first = it0 % a.group, qt_first = qt1 - it0 / a.group;
+  if (niter == 0 && nsplit == 1 && a.accumulate) return;   // nothing visible, nothing to add
 
-  // ---- asynchronous tile fetch (all 8 wavefronts share the copies) ----
-  const char* qbase = reinterpret_cast<const char*>(a.q) + (int64_t)a.q_row0 * a.q_ts * 2;
-  const char* dobase = reinterpret_cast<const char*>(a.d_o) + (int64_t)a.q_row0 * a.Hq * 256;
-  const int64_t q_tile_bytes = (int64_t)kBQ * a.q_ts * 2, do_tile_bytes = (int64_t)kBQ * a.Hq * 256;
-  const DmaOffs<kCopies> qoff_full = dma_n_offsets<kCopies>(a.q_ts, kBQ, wave, lane);
-  const DmaOffs<kCopies> dooff_full = dma_n_offsets<kCopies>((int64_t)a.Hq * 128, kBQ, wave, lane);
-  // Cursor over the (head of the group, query tile) sequence: byte offsets of the tile in the
-  // four sources, advanced by additions so that the loop carries no 64-bit multiplies.
-  struct Cursor { int hg, qt; int64_t q, d_o, img, st; };
-  const int64_t q_head_step = (int64_t)a.q_hs * 2, do_head_step = 256;
-  const int64_t img_head_step = (int64_t)w.n_qtiles * kImageBytes, st_head_step = (int64_t)w.n_qtiles * kBQ * 4;
-  const int gm1 = a.group - 1;
-  auto advance = [&](Cursor& cu) {                       // nsplit elements further in the sequence
-    for (int j = 0; j < nsplit; ++j) {
-      if (++cu.hg == a.group) {                          // next (lower) query tile, first head of the group
-        cu.hg = 0; --cu.qt;
-        cu.q -= gm1 * q_head_step + q_tile_bytes; cu.d_o -= gm1 * do_head_step + do_tile_bytes;
-        cu.img -= gm1 * img_head_step + kImageBytes; cu.st -= gm1 * st_head_step + kBQ * 4;
-      } else {
-        cu.q += q_head_step; cu.d_o += do_head_step; cu.img += img_head_step; cu.st += st_head_step;
-      }
-    }
-  };
-  Cursor fc;                                             // tile whose copies are being issued
-  {
-    const int h0 = kvh * a.group + hg_first;
-    fc.hg = hg_first; fc.qt = qt_first;
-    fc.q = (int64_t)h0 * a.q_hs * 2 + (int64_t)qt_first * q_tile_bytes;
-    fc.d_o = (int64_t)h0 * 256 + (int64_t)qt_first * do_tile_bytes;
-    fc.img = ((int64_t)h0 * w.n_qtiles + qt_first) * kImageBytes;
-    fc.st = ((int64_t)h0 * w.n_qtiles + qt_first) * kBQ * 4;
-  }
-  // The copies of one tile are issued in four pieces (Q with the statistics, dO, Q^T image,
-  // dO^T image) that the loop spreads between its MFMAs: a burst of copy instructions holds
-  // up the issuing wavefronts until the texture path has taken them all.
-  const char* const stat_src = reinterpret_cast<const char*>((wave & 1) ? w.dl : w.nl2) + lane * 4;
-  auto fetch_piece = [&](int piece, const Cursor& cu, char* stage, float* stat) {
-    if (piece < 2) {
-      const int left = a.n_q - cu.qt * kBQ;              // < kBQ: ragged last tile, rows past the end repeat the last row
-      if (piece == 0) {
-        const char* qp = qbase + cu.q;
-        if (left >= kBQ) dma_tile_n<kCopies>(qp, qoff_full, stage, wave);
-        else dma_tile_n<kCopies>(qp, dma_n_offsets<kCopies>(a.q_ts, left, wave, lane), stage, wave);
-        // statistics: even wavefronts fetch -LSE*log2e, odd ones delta (several fetch the same bytes)
-        dma4(stat_src + cu.st, reinterpret_cast<char*>(stat + (wave & 1) * 64));
-      } else {
-        const char* dp = dobase + cu.d_o;
-        if (left >= kBQ) dma_tile_n<kCopies>(dp, dooff_full, stage + kTileBytes, wave);
-        else dma_tile_n<kCopies>(dp, dma_n_offsets<kCopies>((int64_t)a.Hq * 128, left, wave, lane), stage + kTileBytes, wave);
-      }
-    } else {
-      dma_tile_image<kCopies>((piece == 2 ? w.qt : w.dot) + cu.img, stage + piece * kTileBytes, wave, lane);
-    }
-  };
-  if (niter > 0) {
-#pragma unroll
-    for (int piece = 0; piece < 4; ++piece) fetch_piece(piece, fc, stage0, stat0);
-  }
-
-  // K (P role) or V (D role) rows of this lane's key as B operands (k index along d)
-  u32x4 kvreg[8];
+  // K and V rows of this lane's key as B operands (k index along d)
+  u32x4 kreg[8], vreg[8];
   {
     const int64_t off = (int64_t)(a.k_row0 + keyc) * a.kv_ts + (int64_t)kvh * a.kv_hs + half * 8;
-    const uint16_t* p = reinterpret_cast<const uint16_t*>(role_p ? a.k : a.v) + off;
+    const uint16_t* pk = reinterpret_cast<const uint16_t*>(a.k) + off;
+    const uint16_t* pv = reinterpret_cast<const uint16_t*>(a.v) + off;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) kvreg[ks] = *reinterpret_cast<const u32x4*>(p + ks * 16);
+    for (int ks = 0; ks < 8; ++ks) {
+      kreg[ks] = *reinterpret_cast<const u32x4*>(pk + ks * 16);
+      vreg[ks] = *reinterpret_cast<const u32x4*>(pv + ks * 16);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) { MMSP_PIN(kreg[ks]); MMSP_PIN(vreg[ks]); }   // landed before the tile copies are counted
   }
   const float c = a.scale * kLog2e;
 
-  f32x16 acc[4];                                         // dV^T (P role) or dK^T (D role): 128 d x 32 keys
+  f32x16 dv[4], dk[4];                                   // dV^T, dK^T: 128 d x 32 keys
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[db][i] = 0.f;
+    for (int i = 0; i < 16; ++i) { dv[db][i] = 0.f; dk[db][i] = 0.f; }
 
-  // LDS read offsets, fixed for the whole call.  P role reads Q (natural) and dO^T; D role
-  // reads dO (natural) and Q^T.
-  int na[8], ta[4];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) na[ks] = tile_n_offset(col, ks * 2 + half) + (role_p ? 0 : kTileBytes);            // + qb*8192
-#pragma unroll
-  for (int x = 0; x < 4; ++x) ta[x] = tile_t_offset(col, x * 2 + half) + (role_p ? 3 : 2) * kTileBytes;             // + db*4096
-  char* const my_px = pxch + pair * 2048 + lane * 16;    // + slot * 8192; second 16 bytes of the lane at + 1024
-
-  // (head of the group, query tile) of the tile being computed and of the tile whose copies
-  // are being issued.  While tile t is computed: the rest of tile t+1 during its first block,
-  // the first piece of tile t+2 after its second barrier, which frees the stage of tile t.
-  int cur_hg = hg_first, cur_qt = qt_first;
-  if (niter > 0) advance(fc);
-  if (niter > 1) fetch_piece(0, fc, stage1, stat1);
-
-  // LDS operands are fetched a whole product ahead of the MFMAs that use them.  o1 feeds a
-  // block's first product (S or dP); it is reloaded for the next block as soon as the MFMAs
-  // that read it are issued, for the next tile's first block right after the barrier that hands
-  // the stages over.  o2 feeds the second product (dV or dK) and is loaded before the exchange.
-  u32x4 o1[8], o2[8];
-  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): K / V registers and both stages
-  lds_barrier();
   if (niter > 0) {
+    // ---- asynchronous tile fetch: cursor over the (head of the group, query tile) sequence ----
+    const char* qbase = reinterpret_cast<const char*>(a.q) + ((int64_t)a.q_row0 * a.q_ts + (int64_t)kvh * a.group * a.q_hs) * 2;
+    const char* dobase = reinterpret_cast<const char*>(a.d_o) + ((int64_t)a.q_row0 * a.Hq + (int64_t)kvh * a.group) * 256;
+    const int64_t q_tile_bytes = (int64_t)kBQ * a.q_ts * 2, do_tile_bytes = (int64_t)kBQ * a.Hq * 256;
+    const int64_t q_head_bytes = (int64_t)a.q_hs * 2;
+    const int64_t st_head_bytes = (int64_t)w.n_qtiles * kBQ * 4;
+    const char* stat_src = reinterpret_cast<const char*>((wave & 1) ? w.dl : w.nl2) + (int64_t)kvh * a.group * st_head_bytes + lane * 4;
+    const DmaOffs<kCopies> qoff_full = dma_s_offsets<kCopies>(a.q_ts, kBQ, wave, lane);
+    const DmaOffs<kCopies> dooff_full = dma_s_offsets<kCopies>((int64_t)a.Hq * 128, kBQ, wave, lane);
+    int f_hg = split % a.group, f_qt = qt1 - split / a.group, f_it = 0;   // element the next fetch takes
+    // A fetch is issued in 2 kCopies + 1 pieces (one copy instruction each) so that the loop can
+    // spread them between its matrix instructions: a copy holds up the issuing wavefront while
+    // the memory pipeline accepts it, and with one wavefront per SIMD nobody else fills that gap.
+    struct Fetch { const char* q; const char* d_o; const char* st; DmaOffs<kCopies> qo, dd; };
+    auto fetch_begin = [&]() {
+      Fetch f;
+      const int left = a.n_q - f_qt * kBQ;              // < kBQ: ragged last tile, rows past the end repeat the last row
+      f.q = qbase + f_hg * q_head_bytes + f_qt * q_tile_bytes;
+      f.d_o = dobase + f_hg * 256 + f_qt * do_tile_bytes;
+      f.st = stat_src + f_hg * st_head_bytes + f_qt * (kBQ * 4);
+      f.qo = qoff_full; f.dd = dooff_full;
+      if (left < kBQ) {
+        f.qo = dma_s_offsets<kCopies>(a.q_ts, left, wave, lane);
+        f.dd = dma_s_offsets<kCopies>((int64_t)a.Hq * 128, left, wave, lane);
+      }
+      if (f_it + 1 < niter) {                           // past the end the last tile is fetched again (into a free slot)
+        ++f_it;
+        f_hg += nsplit;
+        while (f_hg >= a.group) { f_hg -= a.group; --f_qt; }
+      }
+      return f;
+    };
+    auto fetch_piece = [&](const Fetch& f, int piece, char* qdst, char* odst, float* sdst) {
+      constexpr int W = 16 / kCopies;
+      if (piece < kCopies) dma16(f.q + f.qo.o[piece], qdst + (wave + piece * W) * 1024);
+      else if (piece < 2 * kCopies) dma16(f.d_o + f.dd.o[piece - kCopies], odst + (wave + (piece - kCopies) * W) * 1024);
+      else dma4(f.st, reinterpret_cast<char*>(sdst + (wave & 1) * 64));   // even wavefronts fetch -LSE*log2e, odd ones delta
+    };
+    auto fetch = [&](char* qdst, char* odst, float* sdst) {
+      const Fetch f = fetch_begin();
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(stage0 + na[ks]);
-  }
+      for (int piece = 0; piece < kGroup; ++piece) fetch_piece(f, piece, qdst, odst, sdst);
+    };
+    fetch(qs0, os0, st0);
+    fetch(qs1, os1, st1);
+    fetch(qs2, os2, st2);
 
-  // One tile = two 32-row blocks and two workgroup barriers, one per block: before it the P
-  // wavefronts have published P of the block and everybody has finished every LDS read issued
-  // so far.  The second barrier of a tile therefore also retires the tile's stage, which is
-  // refilled at once with the tile after next, and publishes the next tile's stage (each
-  // wavefront waits for its own copies of it first).
-  auto tile_body = [&](int it, char* cur, float* stat, char* oth, float* ostat) {
-    const int q0 = cur_qt * kBQ;
-    cur_hg += nsplit;
-    while (cur_hg >= a.group) { cur_hg -= a.group; --cur_qt; }
-    const bool need_mask = kMask && (q0 < w_lo_max || q0 + kBQ - 1 > w_hi_min);
+    // LDS read offsets inside a tile, fixed for the whole call: natural operand k-step ks (rows
+    // +32 -> +8192 bytes); transposed operand of d block db, first / second read (16 rows further
+    // -> +4096 bytes)
+    int na[8], ta[4][2];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      // first product of the block: S = Q K^T (P role) or dP = dO V^T (D role)
-      f32x16 x;
+    for (int ks = 0; ks < 8; ++ks) na[ks] = tile_s_offset(col, ks * 2 + half);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) x[i] = 0.f;
+    for (int db = 0; db < 4; ++db) {
+      ta[db][0] = tile_s_tr_offset(lane, db, 0);
+      ta[db][1] = tile_s_tr_offset(lane, db, 1);
+    }
+    const int so = half * 4;                             // statistics of rows (i/4)*8 + half*4 + i%4: float4 at so + 8 g4
+
+    // (head of the group, query tile) of the tile being computed
+    int c_hg = split % a.group, c_qt = qt1 - split / a.group;
+
+    // Software pipeline state carried from block to block.
+    f32x16 s_nx, dp_nx;          // S and dP of the next block (first products, being accumulated)
+    f32x16 p_cur, dp_cur;        // P (fp32) and dP of the current block
+    u32x4 pb0, pb1;              // P of the current block packed as B operands (rows 0..15, 16..31)
+    u32x4 oq[kDepth];            // LDS operands in flight, kDepth matrix instructions deep
+
+    // Operand n of a tile body (one per matrix instruction), read four instructions ahead:
+    //   n =  0..15  phase A of block 0: S / dP of block 1      natural rows 32..63 of this tile (Q even n, dO odd n)
+    //   n = 16..31  phase B of block 0: dV / dK of block 0     transposed rows 0..31 (dO even n, Q odd n)
+    //   n = 32..47  phase A of block 1: S / dP of the next tile's block 0   natural rows 0..31 of the next tile
+    //   n = 48..63  phase B of block 1: dV / dK of block 1     transposed rows 32..63
+    //   n = 64 ...  = the first operands of the next tile body (whose "this tile" is our next tile)
+    auto operand = [&](int n, const char* cq, const char* co, const char* nq, const char* no) -> u32x4 {
+      if (n >= 64) { n -= 64; cq = nq; co = no; }
+      const int ph = n >> 4, i = n & 15;
+      if ((ph & 1) == 0) {                               // natural: k-step i / 2, Q for S (even), dO for dP (odd)
+        const char* t = ph == 0 ? ((i & 1) ? co : cq) : ((i & 1) ? no : nq);
+        return *reinterpret_cast<const u32x4*>(t + na[i >> 1] + (ph == 0 ? 8192 : 0));
+      }
+      // transposed: i = 8 t' + 2 db + (0: dO^T for dV, 1: Q^T for dK)
+      const int tq = i >> 3, db = (i >> 1) & 3, g = (ph == 1 ? 0 : 2) + tq;
+      const char* t = (i & 1) ? cq : co;
+      const u32x2 v0 = lds_read_tr(t + ta[db][0] + g * 4096);
+      const u32x2 v1 = lds_read_tr(t + ta[db][1] + g * 4096);
+      return mk4(v0.x, v0.y, v1.x, v1.y);
+    };
+
+    auto apply_mask = [&](f32x16& x, int q0) {           // q0: first row of the block
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int qrow = q0 + (i >> 2) * 8 + half * 4 + (i & 3);
+        x[i] = (qrow < rlo || qrow > rhi) ? -INFINITY : x[i];
+      }
+    };
+    auto needs_mask = [&](int q0) { return kMask && (q0 < w_lo_max || q0 + 31 > w_hi_min); };
+
+    // ---- prologue: S, dP and P of the first block ----
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * kGroup) & 15) | (((2 * kGroup) >> 4) << 14));   // vmcnt(2 kGroup): the first tile has landed (two newer groups may be in flight)
+    lds_barrier();
+    {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { s_nx[i] = 0.f; dp_nx[i] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        x = mfma32(o1[ks], kvreg[ks], x);
-        if (qb == 0 && (ks == 2 || ks == 5)) {
-          if (it + 1 < niter) fetch_piece(ks == 2 ? 1 : 2, fc, oth, ostat);
-          __builtin_amdgcn_sched_barrier(0);
-        }
+        s_nx = mfma32(*reinterpret_cast<const u32x4*>(qs0 + na[ks]), kreg[ks], s_nx);
+        dp_nx = mfma32(*reinterpret_cast<const u32x4*>(os0 + na[ks]), vreg[ks], dp_nx);
       }
+      if (needs_mask(c_qt * kBQ)) apply_mask(s_nx, c_qt * kBQ);
+      uint32_t pw[8];
 #pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        o2[2 * db] = *reinterpret_cast<const u32x4*>(cur + ta[(qb * 2) ^ db] + db * 4096);
-        o2[2 * db + 1] = *reinterpret_cast<const u32x4*>(cur + ta[(qb * 2 + 1) ^ db] + db * 4096);
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const float4 nl = *reinterpret_cast<const float4*>(st0 + so + g4 * 8);
+        p_cur[g4 * 4 + 0] = __builtin_amdgcn_exp2f(fmaf(s_nx[g4 * 4 + 0], c, nl.x));
+        p_cur[g4 * 4 + 1] = __builtin_amdgcn_exp2f(fmaf(s_nx[g4 * 4 + 1], c, nl.y));
+        p_cur[g4 * 4 + 2] = __builtin_amdgcn_exp2f(fmaf(s_nx[g4 * 4 + 2], c, nl.z));
+        p_cur[g4 * 4 + 3] = __builtin_amdgcn_exp2f(fmaf(s_nx[g4 * 4 + 3], c, nl.w));
+        pw[g4 * 2] = pack2(p_cur[g4 * 4 + 0], p_cur[g4 * 4 + 1]);
+        pw[g4 * 2 + 1] = pack2(p_cur[g4 * 4 + 2], p_cur[g4 * 4 + 3]);
       }
-      if (qb == 0) {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(cur + na[ks] + 8192);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+      pb0 = mk4(pw[0], pw[1], pw[2], pw[3]);
+      pb1 = mk4(pw[4], pw[5], pw[6], pw[7]);
+      dp_cur = dp_nx;
+    }
 
-      u32x4 b0, b1;                                      // B operands of the second product
-      char* px = my_px + qb * 8192;                      // exchange slot of this block
-      if (role_p) {
-        if (need_mask) {
+    // One tile: four phases of 16 matrix instructions.  cq / co / cs: this tile's slot, nq / no / ns:
+    // the next tile's, rq / ro / rs: the slot to refill (three tiles ahead).
+    auto body = [&](bool first, const char* cq, const char* co, const float* cs, const char* nq, const char* no, const float* ns,
+                    char* rq, char* ro, float* rs) {
+      // Own copies of every group but the newest have landed; after the barrier everybody's have
+      // (this tile's and the next one's), and everybody is done with the slot about to be refilled.
+      __builtin_amdgcn_s_waitcnt(0x0F70 | kGroup);
+      lds_barrier();
+      const Fetch fx = fetch_begin();
+      const int q0 = c_qt * kBQ;
+      c_hg += nsplit;
+      while (c_hg >= a.group) { c_hg -= a.group; --c_qt; }
+      const int q0_next = c_qt * kBQ;                    // first row of the next tile (unused after the last)
+      if (first) {
+#pragma unroll
+        for (int n = 0; n < kDepth; ++n) oq[n] = operand(n, cq, co, nq, no);
+      }
+      MMSP_STEP_END();
+
+#pragma unroll
+      for (int ph = 0; ph < 4; ++ph) {
+        const int blk = ph >> 1;                         // block of this tile the phase works for
+        if ((ph & 1) == 0) {
+          // ---- phase A: S, dP of the following block beside dS of block blk ----
+          float4 dl[4];
+#pragma unroll
+          for (int g4 = 0; g4 < 4; ++g4) dl[g4] = *reinterpret_cast<const float4*>(cs + 64 + blk * 32 + so + g4 * 8);
+#pragma unroll
+          for (int i = 0; i < 16; ++i) { s_nx[i] = 0.f; dp_nx[i] = 0.f; }
+          uint32_t sw[8];
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            const int qrow = q0 + qb * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
-            x[i] = (qrow < rlo || qrow > rhi) ? -INFINITY : x[i];
+            const int n = ph * 16 + i, ks = i >> 1;
+            u32x4 op = oq[n & (kDepth - 1)];
+            MMSP_PIN(op);
+            if ((i & 1) == 0) s_nx = mfma32(op, kreg[ks], s_nx);
+            else dp_nx = mfma32(op, vreg[ks], dp_nx);
+            oq[n & (kDepth - 1)] = operand(n + kDepth, cq, co, nq, no);
+            if (n % 7 == 3 && n / 7 < kGroup) fetch_piece(fx, n / 7, rq, ro, rs);
+            if (i >= 4 && i < 12) {                      // dS of rows 2j, 2j+1 of the lane's 16 (one pair per step)
+              const int j = i - 4, e = 2 * j;
+              const float d0 = (e & 3) == 0 ? dl[e >> 2].x : dl[e >> 2].z;
+              const float d1 = (e & 3) == 0 ? dl[e >> 2].y : dl[e >> 2].w;
+              sw[j] = pack2(p_cur[e] * (dp_cur[e] - d0), p_cur[e + 1] * (dp_cur[e + 1] - d1));
+              MMSP_PIN(sw[j]);
+            }
+            if ((i & 1) == 0) MMSP_PIN_ACC(s_nx); else MMSP_PIN_ACC(dp_nx);
+            MMSP_STEP_END();
           }
-        }
-        uint32_t pw[8];
+          // hand over: the packed dS of block blk feeds phase B; S / dP of the following block become current
+          const u32x4 ds0 = mk4(sw[0], sw[1], sw[2], sw[3]), ds1 = mk4(sw[4], sw[5], sw[6], sw[7]);
+          const int q0_f = blk == 0 ? q0 + 32 : q0_next;  // first row of the following block
+          if (needs_mask(q0_f)) apply_mask(s_nx, q0_f);
+          MMSP_STEP_END();
+          // ---- phase B: dV, dK of block blk beside P of the following block ----
+          const float* fs = blk == 0 ? cs + 32 : ns;     // -LSE*log2e of the following block's rows
+          float4 nl[4];
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          const float4 nl = *reinterpret_cast<const float4*>(stat + qb * 32 + g4 * 8 + half * 4);
-          pw[g4 * 2] = pack2(__builtin_amdgcn_exp2f(fmaf(x[g4 * 4 + 0], c, nl.x)),
-                             __builtin_amdgcn_exp2f(fmaf(x[g4 * 4 + 1], c, nl.y)));
-          pw[g4 * 2 + 1] = pack2(__builtin_amdgcn_exp2f(fmaf(x[g4 * 4 + 2], c, nl.z)),
-                                 __builtin_amdgcn_exp2f(fmaf(x[g4 * 4 + 3], c, nl.w)));
-        }
-        b0 = mk4(pw[0], pw[1], pw[2], pw[3]);
-        b1 = mk4(pw[4], pw[5], pw[6], pw[7]);
-        *reinterpret_cast<u32x4*>(px) = b0;
-        *reinterpret_cast<u32x4*>(px + 1024) = b1;
-      } else {
-        // dP - delta before the barrier: the statistics belong to the stage being retired
+          for (int g4 = 0; g4 < 4; ++g4) nl[g4] = *reinterpret_cast<const float4*>(fs + so + g4 * 8);
+          uint32_t pw[8];
+          f32x16 p_nx;
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          const float4 dl = *reinterpret_cast<const float4*>(stat + 64 + qb * 32 + g4 * 8 + half * 4);
-          x[g4 * 4 + 0] -= dl.x; x[g4 * 4 + 1] -= dl.y; x[g4 * 4 + 2] -= dl.z; x[g4 * 4 + 3] -= dl.w;
-        }
-      }
-      if (qb == 0) {
-        lds_barrier_after_write();
-      } else {
-        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): own copies of the next tile
-        lds_barrier_after_write();
-        if (it + 1 < niter) {
-#pragma unroll
-          for (int ks = 0; ks < 8; ++ks) o1[ks] = *reinterpret_cast<const u32x4*>(oth + na[ks]);
-        }
-      }
-      if (!role_p) {
-        const u32x4 p0 = *reinterpret_cast<const u32x4*>(px);
-        const u32x4 p1 = *reinterpret_cast<const u32x4*>(px + 1024);
-        const uint32_t pw[8] = {p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
-        uint32_t sw[8];
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          const float pa = __uint_as_float(pw[g4 * 2] << 16), pb_ = __uint_as_float(pw[g4 * 2] & 0xffff0000u);
-          const float pc = __uint_as_float(pw[g4 * 2 + 1] << 16), pd = __uint_as_float(pw[g4 * 2 + 1] & 0xffff0000u);
-          sw[g4 * 2] = pack2(pa * x[g4 * 4 + 0], pb_ * x[g4 * 4 + 1]);
-          sw[g4 * 2 + 1] = pack2(pc * x[g4 * 4 + 2], pd * x[g4 * 4 + 3]);
-        }
-        b0 = mk4(sw[0], sw[1], sw[2], sw[3]);
-        b1 = mk4(sw[4], sw[5], sw[6], sw[7]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      // second product: dV^T += dO^T P (P role) or dK^T += Q^T dS (D role)
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        acc[db] = mfma32(o2[2 * db], b0, acc[db]);
-        acc[db] = mfma32(o2[2 * db + 1], b1, acc[db]);
-        if (db == 1) {
-          if (qb == 0) {
-            if (it + 1 < niter) fetch_piece(3, fc, oth, ostat);
-            advance(fc);
-          } else if (it + 2 < niter) {
-            fetch_piece(0, fc, cur, stat);
+          for (int i = 0; i < 16; ++i) {
+            const int n = (ph + 1) * 16 + i, tq = i >> 3, db = (i >> 1) & 3;
+            u32x4 op = oq[n & (kDepth - 1)];
+            MMSP_PIN(op);
+            if ((i & 1) == 0) dv[db] = mfma32(op, tq ? pb1 : pb0, dv[db]);
+            else dk[db] = mfma32(op, tq ? ds1 : ds0, dk[db]);
+            oq[n & (kDepth - 1)] = operand(n + kDepth, cq, co, nq, no);
+            if (n % 7 == 3 && n / 7 < kGroup) fetch_piece(fx, n / 7, rq, ro, rs);
+            if (i >= 4 && i < 12) {                      // P of rows 2j, 2j+1
+              const int j = i - 4, e = 2 * j;
+              const float n0 = (e & 3) == 0 ? nl[e >> 2].x : nl[e >> 2].z;
+              const float n1 = (e & 3) == 0 ? nl[e >> 2].y : nl[e >> 2].w;
+              p_nx[e] = __builtin_amdgcn_exp2f(fmaf(s_nx[e], c, n0));
+              p_nx[e + 1] = __builtin_amdgcn_exp2f(fmaf(s_nx[e + 1], c, n1));
+              pw[j] = pack2(p_nx[e], p_nx[e + 1]);
+              MMSP_PIN(pw[j]);
+            }
+            if ((i & 1) == 0) MMSP_PIN_ACC(dv[db]); else MMSP_PIN_ACC(dk[db]);
+            MMSP_STEP_END();
           }
-          __builtin_amdgcn_sched_barrier(0);
+          pb0 = mk4(pw[0], pw[1], pw[2], pw[3]);
+          pb1 = mk4(pw[4], pw[5], pw[6], pw[7]);
+          p_cur = p_nx;
+          dp_cur = dp_nx;
+          MMSP_STEP_END();
         }
       }
-    }
-  };
+    };
 
-  // Two bodies per trip so that LDS offsets are immediates; the odd last tile is peeled so
-  // that no accumulator crosses a conditional inside the loop.
-  int it = 0;
-  for (; it + 1 < niter; it += 2) {
-    tile_body(it, stage0, stat0, stage1, stat1);
-    tile_body(it + 1, stage1, stat1, stage0, stat0);
+    // Four tiles per trip so that every slot is a compile-time constant; the steady-state loop
+    // has no conditional bodies.
+    int it = 0;
+    for (; it + 3 < niter; it += 4) {
+      body(it == 0, qs0, os0, st0, qs1, os1, st1, qs3, os3, st3);
+      body(false, qs1, os1, st1, qs2, os2, st2, qs0, os0, st0);
+      body(false, qs2, os2, st2, qs3, os3, st3, qs1, os1, st1);
+      body(false, qs3, os3, st3, qs0, os0, st0, qs2, os2, st2);
+    }
+    if (it < niter) {
+      body(it == 0, qs0, os0, st0, qs1, os1, st1, qs3, os3, st3);
+      if (it + 1 < niter) body(false, qs1, os1, st1, qs2, os2, st2, qs0, os0, st0);
+      if (it + 2 < niter) body(false, qs2, os2, st2, qs3, os3, st3, qs1, os1, st1);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                  // drain the copies issued past the end before the workgroup leaves
   }
-  if (it < niter) tile_body(it, stage0, stat0, stage1, stat1);
 
   if (!live) return;
-  const float mul = role_p ? 1.f : a.scale;
   if (nsplit > 1) {                                      // partial result of this range, summed by dkdv_reduce_kernel
     const int64_t slot_elems = (int64_t)n_kt * kKeys * a.Hkv * 128;
-    float* out = w.partial + ((int64_t)(role_p ? nsplit : 0) + split) * slot_elems + ((int64_t)key * a.Hkv + kvh) * 128 + half * 4;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int which = 0; which < 2; ++which) {
+      const float mul = which ? 1.f : a.scale;
+      float* out = w.partial + ((int64_t)(which ? nsplit : 0) + split) * slot_elems + ((int64_t)key * a.Hkv + kvh) * 128 + half * 4;
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4)
-        *reinterpret_cast<float4*>(out + db * 32 + g4 * 8) =
-            make_float4(mul * acc[db][g4 * 4 + 0], mul * acc[db][g4 * 4 + 1], mul * acc[db][g4 * 4 + 2], mul * acc[db][g4 * 4 + 3]);
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const f32x16& x = which ? dv[db] : dk[db];
+          *reinterpret_cast<float4*>(out + db * 32 + g4 * 8) =
+              make_float4(mul * x[g4 * 4 + 0], mul * x[g4 * 4 + 1], mul * x[g4 * 4 + 2], mul * x[g4 * 4 + 3]);
+        }
+    }
     return;
   }
   const int64_t off = ((int64_t)(a.k_row0 + key) * a.Hkv + kvh) * 128 + half * 4;
-  float* out = (role_p ? a.dv : a.dk) + off;
 #pragma unroll
-  for (int db = 0; db < 4; ++db)
+  for (int which = 0; which < 2; ++which) {
+    const float mul = which ? 1.f : a.scale;
+    float* out = (which ? a.dv : a.dk) + off;
 #pragma unroll
-    for (int g4 = 0; g4 < 4; ++g4) {
-      float4* p = reinterpret_cast<float4*>(out + db * 32 + g4 * 8);
-      float4 x = make_float4(mul * acc[db][g4 * 4 + 0], mul * acc[db][g4 * 4 + 1], mul * acc[db][g4 * 4 + 2],
-                             mul * acc[db][g4 * 4 + 3]);
-      if (a.accumulate) {
-        const float4 o = *p;
-        x.x += o.x; x.y += o.y; x.z += o.z; x.w += o.w;
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const f32x16& x = which ? dv[db] : dk[db];
+        float4* p = reinterpret_cast<float4*>(out + db * 32 + g4 * 8);
+        float4 y = make_float4(mul * x[g4 * 4 + 0], mul * x[g4 * 4 + 1], mul * x[g4 * 4 + 2], mul * x[g4 * 4 + 3]);
+        if (a.accumulate) {
+          const float4 o = *p;
+          y.x += o.x; y.y += o.y; y.z += o.z; y.w += o.w;
+        }
+        *p = y;
       }
-      *p = x;
-    }
+  }
 }
+#undef MMSP_PIN
+#undef MMSP_PIN_ACC
+#undef MMSP_STEP_END
 
 // out[i] (+)= sum over the nsplit partial slots, for the n4 float4 of dK (blockIdx.y = 0) or dV (1).
 __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const float* __restrict__ partial, int nsplit, int64_t slot_elems,

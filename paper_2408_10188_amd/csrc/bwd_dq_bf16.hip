@@ -3,9 +3,9 @@
 // Same skeleton as the forward kernel: a workgroup is 8 wavefronts = 256 query rows of one
 // head, two wavefronts per SIMD; wavefront w owns 32 rows and keeps their Q and dO (MFMA B
 // operands), the dQ^T accumulator (128 d x 32 queries) and the two row statistics (-LSE*log2e,
-// delta) in registers for the whole call.  64-key tiles of K, V (natural orientation) and the
-// pre-transposed K^T tile image stream through a three-stage LDS ring filled by asynchronous
-// global->LDS copies.
+// delta) in registers for the whole call.  64-key tiles of K and V stream through a three-stage
+// LDS ring filled by asynchronous global->LDS copies straight from the caller's tensors (natural
+// orientation; the third product reads K back transposed with ds_read_b64_tr_b16).
 //   S^T[key][query]  = K . Q^T            P^T = exp2(S^T * c - LSE*log2e)   (final LSE: no running max)
 //   dP^T[key][query] = V . dO^T           dS^T = P^T * (dP^T - delta)
 //   dQ^T[d][query]  += K^T . dS^T         (B operand = dS^T straight from registers)
@@ -20,13 +20,16 @@ constexpr int kWaves = 8;
 constexpr int kBM = 32 * kWaves;   // query rows per workgroup
 constexpr int kBN = 64;            // keys per tile
 constexpr int kCopies = 16 / kWaves;
-constexpr int kStageBytes = 3 * kTileBytes;   // K TileN | V TileN | K^T TileT
 
-__global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a, const char* kt_images, int n_qt,
-                                                                     int xcd_per_kv) {
-  __shared__ __attribute__((aligned(1024))) char stage0[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) char stage1[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) char stage2[kStageBytes];
+__global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a, int n_qt, int xcd_per_kv) {
+  // One array per tile and ring slot, selected at compile time, so that the compiler can tell
+  // the reads of one slot from the copies in flight into another.
+  __shared__ __attribute__((aligned(1024))) char ks0[kTileBytes];   // K tiles, TileS
+  __shared__ __attribute__((aligned(1024))) char ks1[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char ks2[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char vs0[kTileBytes];   // V tiles, TileS
+  __shared__ __attribute__((aligned(1024))) char vs1[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char vs2[kTileBytes];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, col = lane & 31;
@@ -68,24 +71,43 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
   const int64_t kv_off = ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
   const char* kbase = reinterpret_cast<const char*>(a.k) + kv_off;
   const char* vbase = reinterpret_cast<const char*>(a.v) + kv_off;
-  const char* kimg = kt_images + (int64_t)kvh * tiles_of(a.n_k) * kImageBytes;
   const int64_t tile_bytes = (int64_t)kBN * a.kv_ts * 2;
-  const DmaOffs<kCopies> off_full = dma_n_offsets<kCopies>(a.kv_ts, kBN, wave, lane);
-  auto fetch = [&](int kt, char* stage) {
-    const int left = a.n_k - kt * kBN;
-    const int64_t t = (int64_t)kt * tile_bytes;
-    if (left >= kBN) {
-      dma_tile_n<kCopies>(kbase + t, off_full, stage, wave);
-      dma_tile_n<kCopies>(vbase + t, off_full, stage + kTileBytes, wave);
-    } else {                                            // ragged last tile: rows past the end repeat the last row
-      const DmaOffs<kCopies> off = dma_n_offsets<kCopies>(a.kv_ts, left, wave, lane);
-      dma_tile_n<kCopies>(kbase + t, off, stage, wave);
-      dma_tile_n<kCopies>(vbase + t, off, stage + kTileBytes, wave);
+  // Per-lane source addresses of the next tile to fetch, carried from tile to tile and advanced
+  // by additions.  (They stay in the same registers for the whole loop: a copy's address
+  // register that is recycled for an LDS read right behind it makes the compiler wait for every
+  // copy in flight.)
+  const char* pk[kCopies];
+  const char* pv[kCopies];
+  int f_kt = kt0;                                       // tile the next fetch takes
+  auto point_at = [&](int kt) {
+    const DmaOffs<kCopies> off = dma_s_offsets<kCopies>(a.kv_ts, min(kBN, a.n_k - kt * kBN), wave, lane);   // ragged last tile: rows past the end repeat the last row
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) {
+      pk[i] = kbase + (int64_t)kt * tile_bytes + off.o[i];
+      pv[i] = vbase + (int64_t)kt * tile_bytes + off.o[i];
     }
-    dma_tile_image<kCopies>(kimg + (int64_t)kt * kImageBytes, stage + 2 * kTileBytes, wave, lane);
   };
-  if (kt0 <= kt1) fetch(kt0, stage0);
-  if (kt0 + 1 <= kt1) fetch(kt0 + 1, stage1);
+  auto fetch = [&](char* kdst, char* vdst) {            // past the end the last tile is fetched again
+    constexpr int W = 16 / kCopies;
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) dma16(pk[i], kdst + (wave + i * W) * 1024);
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) dma16(pv[i], vdst + (wave + i * W) * 1024);
+    if (f_kt < kt1) {
+      ++f_kt;
+      if (a.n_k - f_kt * kBN >= kBN) {
+#pragma unroll
+        for (int i = 0; i < kCopies; ++i) { pk[i] += tile_bytes; pv[i] += tile_bytes; }
+      } else {
+        point_at(f_kt);
+      }
+    }
+  };
+  if (kt0 <= kt1) {
+    point_at(kt0);
+    fetch(ks0, vs0);
+    fetch(ks1, vs1);
+  }
 
   // Q and dO as B operands: k-step ks covers d = ks*16 .. +16, this lane holds 8 of them
   const int64_t r = a.q_row0 + rowc;
@@ -110,20 +132,26 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
 #pragma unroll
     for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
 
-  // LDS read offsets inside a stage, fixed for the whole call: K / V operand k-step ks (rows
-  // +32 -> +8192 bytes, V tile +16 KiB), K^T operand chunk pair x = g ^ db (d block db -> +4096)
-  int ka[8], ta[4];
+  // LDS read offsets inside a tile, fixed for the whole call: K / V operand k-step ks (rows
+  // +32 -> +8192 bytes); K^T operand of d block db, first / second transposing
+  // read (16 keys further -> +4096 bytes)
+  int ka[8], ta[4][2];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) ka[ks] = tile_n_offset(col, ks * 2 + half);
+  for (int ks = 0; ks < 8; ++ks) ka[ks] = tile_s_offset(col, ks * 2 + half);
 #pragma unroll
-  for (int x = 0; x < 4; ++x) ta[x] = 2 * kTileBytes + tile_t_offset(col, x * 2 + half);
+  for (int db = 0; db < 4; ++db) {
+    ta[db][0] = tile_s_tr_offset(lane, db, 0);
+    ta[db][1] = tile_s_tr_offset(lane, db, 1);
+  }
 
-  auto tile_body = [&](int kt, const char* cur, char* refill) {
+  auto tile_body = [&](int kt, const char* kcur, const char* vcur, char* krefill, char* vrefill) {
     // Own copies of tile kt have landed (the newest tile's may still be in flight); after the
-    // barrier everybody's have, and everybody is done with the stage about to be refilled.
-    if (kt < kt1) __builtin_amdgcn_s_waitcnt(0x0F70 | (3 * kCopies)); else __builtin_amdgcn_s_waitcnt(0x0F70);
+    // barrier everybody's have, and everybody is done with the stage about to be refilled.  Every
+    // tile issues one whole group of copies (past the end it fetches the last tile again, into a
+    // stage nobody reads any more), so the wait is the same constant everywhere.
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * kCopies));
     lds_barrier();
-    if (kt + 2 <= kt1) fetch(kt + 2, refill);
+    fetch(krefill, vrefill);
     const int k0 = kt * kBN;
     const bool need_mask = k0 < w_lo_max || k0 + kBN - 1 > w_hi_min;
 
@@ -134,16 +162,19 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
       for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        s = mfma32(*reinterpret_cast<const u32x4*>(cur + ka[ks] + kb * 8192), qreg[ks], s);
-        dp = mfma32(*reinterpret_cast<const u32x4*>(cur + kTileBytes + ka[ks] + kb * 8192), doreg[ks], dp);
+        s = mfma32(*reinterpret_cast<const u32x4*>(kcur + ka[ks] + kb * 8192), qreg[ks], s);
+        dp = mfma32(*reinterpret_cast<const u32x4*>(vcur + ka[ks] + kb * 8192), doreg[ks], dp);
       }
       // K^T operands of the third product: issued now, they land during the exp / dS arithmetic
       u32x4 top[8];
 #pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        top[2 * db] = *reinterpret_cast<const u32x4*>(cur + ta[(kb * 2) ^ db] + db * 4096);
-        top[2 * db + 1] = *reinterpret_cast<const u32x4*>(cur + ta[(kb * 2 + 1) ^ db] + db * 4096);
-      }
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int tq = 0; tq < 2; ++tq) {
+          const u32x2 v0 = lds_read_tr(kcur + ta[db][0] + (kb * 2 + tq) * 4096);
+          const u32x2 v1 = lds_read_tr(kcur + ta[db][1] + (kb * 2 + tq) * 4096);
+          top[2 * db + tq] = mk4(v0.x, v0.y, v1.x, v1.y);
+        }
       __builtin_amdgcn_sched_barrier(0);
       if (need_mask) {
 #pragma unroll
@@ -169,12 +200,20 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
     }
   };
 
-  // Three bodies per trip so that every LDS offset is a compile-time constant.
-  for (int kt = kt0; kt <= kt1; kt += 3) {
-    tile_body(kt, stage0, stage2);
-    if (kt + 1 <= kt1) tile_body(kt + 1, stage1, stage0);
-    if (kt + 2 <= kt1) tile_body(kt + 2, stage2, stage1);
+  // Three bodies per trip so that every stage is a compile-time constant (the compiler then sees
+  // that the reads of one stage cannot alias the copies in flight into another); the
+  // steady-state loop has no conditional bodies.
+  int kt = kt0;
+  for (; kt + 2 <= kt1; kt += 3) {
+    tile_body(kt, ks0, vs0, ks2, vs2);
+    tile_body(kt + 1, ks1, vs1, ks0, vs0);
+    tile_body(kt + 2, ks2, vs2, ks1, vs1);
   }
+  if (kt <= kt1) {
+    tile_body(kt, ks0, vs0, ks2, vs2);
+    if (kt + 1 <= kt1) tile_body(kt + 1, ks1, vs1, ks0, vs0);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);                    // drain the copies issued past the end
 
   if (!live) return;
   float* out = a.dq + ((int64_t)(a.q_row0 + row) * a.Hq + h) * 128 + half * 4;
@@ -192,20 +231,14 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
 
 }  // namespace
 
-int64_t bwd_dq_bf16_workspace_bytes(int Hkv, int64_t n_k) { return (int64_t)Hkv * tiles_of(n_k) * kImageBytes; }
-
-// kt_images: room for bwd_dq_bf16_workspace_bytes(Hkv, n_k) bytes, filled here with the K^T
-// tile images of the visiting block.
-hipError_t launch_bwd_dq_bf16(const StepArgs& a, char* kt_images, hipStream_t stream) {
-  hipError_t e = launch_transpose_tiles(a.k, a.kv_ts, a.kv_hs, a.Hkv, a.k_row0, a.n_k, kt_images, stream);
-  if (e != hipSuccess) return e;
+hipError_t launch_bwd_dq_bf16(const StepArgs& a, hipStream_t stream) {
   const int n_qt = (a.n_q + kBM - 1) / kBM;
   int xcd_per_kv = 0, n_blocks = n_qt * a.Hq;
   if (8 % a.Hkv == 0) {
     xcd_per_kv = 8 / a.Hkv;
     n_blocks = 8 * ((a.group * n_qt + xcd_per_kv - 1) / xcd_per_kv);
   }
-  bwd_dq_bf16_kernel<<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, kt_images, n_qt, xcd_per_kv);
+  bwd_dq_bf16_kernel<<<dim3(n_blocks), dim3(64 * kWaves), 0, stream>>>(a, n_qt, xcd_per_kv);
   return hipGetLastError();
 }
 

@@ -28,20 +28,17 @@ struct StepArgs {
   int32_t mask;                 // 0 full, 1 causal-diag
   int32_t n_docs;
   int32_t accumulate;           // fwd: merge into running state; bwd: add to dk/dv
-  char* ws;                     // caller's workspace (bf16 kernels)
+  char* ws;                     // caller's workspace (bf16 backward)
 };
 
 // Workspace views of one backward call (all inside the caller's workspace).
 struct BwdWorkspace {
-  const char* qt;      // Q^T tile images   [Hq][n_qtiles][16 KiB]
-  const char* dot;     // dO^T tile images  [Hq][n_qtiles][16 KiB]
   const float* nl2;    // -LSE*log2e, [Hq][n_qtiles*64], -inf where LSE = -inf and in the padding
   const float* dl;     // delta,      [Hq][n_qtiles*64], 0 in the padding
   float* partial;      // partial dK then dV of split key tiles, bwd_dkdv_partial_bytes() in all
   int32_t n_qtiles;
 };
 
-constexpr int64_t kImageBytes = 16384;                       // one transposed 64x128 bf16 tile
 __host__ __device__ inline int64_t tiles_of(int64_t rows) { return (rows + 63) / 64; }
 
 // Visible key interval [lo, hi] (indices inside the block's key range, already clipped to
@@ -95,20 +92,13 @@ hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const
 hipError_t launch_delta(const void* o_final, const void* d_o, float* delta, int io_dtype,
                         int64_t lse_hs, int Hq, int d, int row0, int n_rows, hipStream_t stream);
 
-// Builds, for every 64-row tile and head of a [rows, H, 128] bf16 tensor, the 16 KiB image of
-// the transposed LDS tile (TileT) in `out` at ((head * n_tiles + tile) * 16384).
-hipError_t launch_transpose_tiles(const void* x, int64_t tok_stride, int64_t head_stride, int H, int row0, int n_rows,
-                                  void* out, hipStream_t stream);
-
 // Padded per-row statistics of the backward: nl2 = -LSE*log2e (or -inf), dl = delta.
 hipError_t launch_bwd_stats(const float* lse, const float* delta, int64_t lse_hs, int Hq, int row0, int n_rows,
                             float* nl2, float* dl, hipStream_t stream);
 hipError_t launch_bwd_dkdv_bf16(const StepArgs& a, const BwdWorkspace& w, hipStream_t stream);
 int64_t bwd_bf16_workspace_bytes(int Hq, int64_t n_q);
 int64_t bwd_dkdv_partial_bytes();
-hipError_t launch_bwd_dq_bf16(const StepArgs& a, char* kt_images, hipStream_t stream);
-int64_t bwd_dq_bf16_workspace_bytes(int Hkv, int64_t n_k);
-int64_t bwd_bf16_total_workspace_bytes(int Hq, int Hkv, int64_t n_q, int64_t n_k);
+hipError_t launch_bwd_dq_bf16(const StepArgs& a, hipStream_t stream);
 hipError_t bwd_bf16_prepare(const StepArgs& a, BwdWorkspace& w, hipStream_t stream);
 
 hipError_t launch_zigzag_gather(const void* seq, void* shards, int64_t T, int N, int64_t row_bytes, hipStream_t stream);

@@ -1,15 +1,21 @@
 // Forward ring step on bf16 matrix cores, head_dim 128.
 //
-// Workgroup = 8 wavefronts = 256 query rows of one head (two wavefronts per SIMD, so one
-// wavefront's softmax arithmetic overlaps the other's matrix work).  Wavefront w owns 32 rows
-// and keeps their Q (MFMA B operands, 32 VGPRs), the O^T accumulator (128 d x 32 queries, 64
-// VGPRs) and the softmax statistics in registers for the whole call.  K and V^T tiles of 64
-// keys stream through a three-stage LDS ring filled by asynchronous global->LDS copies: K
-// straight from the caller's tensor (swizzled by permuting which chunk a lane fetches), V^T
-// from the pre-transposed tile images in the workspace.
+// Workgroup = 8 wavefronts = 256 query rows of one head, two wavefronts per SIMD.  Wavefront w
+// owns 32 rows and keeps their Q (MFMA B operands, 32 VGPRs), the O^T accumulator (128 d x 32
+// queries, 64 VGPRs) and the softmax statistics in registers for the whole call.  K and V tiles
+// of 64 keys stream through two three-slot LDS rings filled by asynchronous global->LDS copies
+// straight from the caller's tensors (one natural-orientation copy each; V is read back
+// transposed by ds_read_b64_tr_b16).
 //   S^T[key][query] = K . Q^T            (A = K tile from LDS, B = Q registers)
 //   online softmax down the key axis, which is in-lane in S^T's register layout
-//   O^T[d][query]  += V^T . P^T          (A = V^T tile from LDS, B = P^T straight from registers)
+//   O^T[d][query]  += V^T . P^T          (A = V tile read transposed, B = P^T straight from registers)
+//
+// One matrix instruction occupies a SIMD's matrix pipe for 32 cycles but its issue port for
+// only about 8: up to five or six ordinary vector instructions fit beside it if they are
+// independent and interleaved in program order.  The loop is therefore software-pipelined inside
+// every wavefront: while the matrix pipe works on P.V of tile t-1 the vector units take the
+// maximum and the first half of the exponentials of tile t, and while it works on S of tile t+1
+// they take the second half.  Scheduling-group barriers pin that interleaving.
 // Tiles wholly outside every row's visible key interval are skipped; only tiles that cut an
 // interval boundary (the causal diagonal, a document start) pay for masking.
 #include "mfma_tiles.h"
@@ -21,17 +27,19 @@ constexpr int kWaves = 8;
 constexpr int kBM = 32 * kWaves;   // query rows per workgroup
 constexpr int kBN = 64;            // keys per tile
 constexpr int kCopies = 16 / kWaves;
-constexpr int kStageBytes = 2 * kTileBytes;
-
-// vmcnt(n) with expcnt / lgkmcnt left alone
-__device__ __forceinline__ void wait_vmcnt_0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-__device__ __forceinline__ void wait_vmcnt_tile() { __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * kCopies)); }
+constexpr int kSlots = 3;
 
 template <bool kAccum>
 __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, int n_qt, int xcd_per_kv) {
-  __shared__ __attribute__((aligned(1024))) char stage0[kStageBytes];   // K TileN | V^T TileT
-  __shared__ __attribute__((aligned(1024))) char stage1[kStageBytes];
-  __shared__ __attribute__((aligned(1024))) char stage2[kStageBytes];
+  // Tile j (counted from the first visible tile) lives in slot j % 3 of its ring.  One array per
+  // slot, selected at compile time: the compiler then sees that the reads of one slot cannot
+  // alias the copies still in flight into another and does not wait for them.
+  __shared__ __attribute__((aligned(1024))) char kslot0[kTileBytes];   // K tiles, TileS
+  __shared__ __attribute__((aligned(1024))) char kslot1[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char kslot2[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char vslot0[kTileBytes];   // V tiles, TileS
+  __shared__ __attribute__((aligned(1024))) char vslot1[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char vslot2[kTileBytes];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int half = lane >> 5, col = lane & 31;
@@ -69,22 +77,57 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
     key_interval_of_row(a, wr0, dummy, w_hi_min);
     key_interval_of_row(a, wr1, w_lo_max, dummy);
   }
-  const int kt0 = t_lo / kBN, kt1 = t_hi >= t_lo ? t_hi / kBN : kt0 - 1;   // inclusive tile range
+  int kt0 = t_lo / kBN, kt1 = t_hi >= t_lo ? t_hi / kBN : kt0 - 1;   // inclusive tile range
+  kt0 = __builtin_amdgcn_readfirstlane(kt0);
+  kt1 = __builtin_amdgcn_readfirstlane(kt1);
+  w_lo_max = __builtin_amdgcn_readfirstlane(w_lo_max);
+  w_hi_min = __builtin_amdgcn_readfirstlane(w_hi_min);
 
   // ---- asynchronous tile fetch ----
   const char* kbase = reinterpret_cast<const char*>(a.k) + ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
-  const char* vimg = a.ws + (int64_t)kvh * tiles_of(a.n_k) * kImageBytes;
+  const char* vbase = reinterpret_cast<const char*>(a.v) + ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
   const int64_t tile_bytes = (int64_t)kBN * a.kv_ts * 2;
-  const DmaOffs<kCopies> off_full = dma_n_offsets<kCopies>(a.kv_ts, kBN, wave, lane);
-  auto fetch = [&](int kt, char* stage) {
-    const int left = a.n_k - kt * kBN;
-    const char* kp = kbase + (int64_t)kt * tile_bytes;
-    if (left >= kBN) dma_tile_n<kCopies>(kp, off_full, stage, wave);
-    else dma_tile_n<kCopies>(kp, dma_n_offsets<kCopies>(a.kv_ts, left, wave, lane), stage, wave);   // ragged last tile
-    dma_tile_image<kCopies>(vimg + (int64_t)kt * kImageBytes, stage + kTileBytes, wave, lane);
+  // Per-lane source addresses of the next K tile and the next V tile to fetch, carried from tile
+  // to tile and advanced by additions.  (They stay in the same registers for the whole loop: a
+  // copy's address register that is recycled for an LDS read right behind it makes the compiler
+  // wait for every copy in flight.)
+  struct Cursor { const char* p[kCopies]; int kt; };
+  auto point_at = [&](Cursor& cu, const char* base, int kt) {
+    const DmaOffs<kCopies> off = dma_s_offsets<kCopies>(a.kv_ts, min(kBN, a.n_k - kt * kBN), wave, lane);   // ragged last tile: rows past the end repeat the last row
+    cu.kt = kt;
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) cu.p[i] = base + (int64_t)kt * tile_bytes + off.o[i];
   };
-  if (kt0 <= kt1) fetch(kt0, stage0);
-  if (kt0 + 1 <= kt1) fetch(kt0 + 1, stage1);
+  auto fetch = [&](Cursor& cu, const char* base, char* dst) {   // the cursor's tile -> slot dst; past the end the last tile again
+    constexpr int W = 16 / kCopies;
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) dma16(cu.p[i], dst + (wave + i * W) * 1024);
+    if (cu.kt < kt1) {
+      if (a.n_k - (cu.kt + 1) * kBN >= kBN) {
+        ++cu.kt;
+#pragma unroll
+        for (int i = 0; i < kCopies; ++i) cu.p[i] += tile_bytes;
+      } else {
+        point_at(cu, base, cu.kt + 1);
+      }
+    }
+  };
+  // Copies are issued in groups of 2 kCopies per wavefront so that "all but the newest group"
+  // is one s_waitcnt value: {K(kt0), V(kt0)}, {K(kt0+1), K(kt0+2)}, then {K(t+3), V(t+1)} at the
+  // top of iteration t.
+  const bool any_tile = kt0 <= kt1;
+  Cursor kc, vc;
+  if (any_tile) {
+    point_at(kc, kbase, kt0);
+    point_at(vc, vbase, kt0);
+    fetch(kc, kbase, kslot0);
+    fetch(vc, vbase, vslot0);
+    fetch(kc, kbase, kslot1);
+    fetch(kc, kbase, kslot2);
+    // the first iteration multiplies an all-zero P with "the tile before the first": finite zeros
+    *reinterpret_cast<u32x4*>(vslot2 + tid * 32) = mk4(0u, 0u, 0u, 0u);
+    *reinterpret_cast<u32x4*>(vslot2 + tid * 32 + 16) = mk4(0u, 0u, 0u, 0u);
+  }
 
   // Q as B operands: k-step ks covers d = ks*16 .. +16, this lane holds 8 of them
   u32x4 qreg[8];
@@ -110,50 +153,53 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
   const float c = a.scale * kLog2e;
   const float lazy_raw = kLazy / c;
 
-  // LDS read offsets inside a stage, fixed for the whole call: K operand k-step ks (rows +32 ->
-  // +8192 bytes), V^T operand chunk pair x = g ^ db (d block db -> +4096 bytes)
-  int ka[8], va[4];
+  // LDS read offsets inside a tile, fixed for the whole call: K operand k-step ks (keys +32 ->
+  // +8192 bytes); V^T operand of d block db, first / second read (16 keys further -> +4096 bytes)
+  int ka[8], va[4][2];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) ka[ks] = tile_n_offset(col, ks * 2 + half);
+  for (int ks = 0; ks < 8; ++ks) ka[ks] = tile_s_offset(col, ks * 2 + half);
 #pragma unroll
-  for (int x = 0; x < 4; ++x) va[x] = kTileBytes + tile_t_offset(col, x * 2 + half);
+  for (int db = 0; db < 4; ++db) {
+    va[db][0] = tile_s_tr_offset(lane, db, 0);
+    va[db][1] = tile_s_tr_offset(lane, db, 1);
+  }
 
-  auto tile_body = [&](int kt, const char* cur, char* refill) {
-    // Own copies of tile kt have landed (the newest tile's may still be in flight); after the
-    // barrier everybody's have, and everybody is done with the stage about to be refilled.
-    if (kt < kt1) wait_vmcnt_tile(); else wait_vmcnt_0();
-    lds_barrier();
-    if (kt + 2 <= kt1) fetch(kt + 2, refill);
-    const int k0 = kt * kBN;
-
-    // ---- S^T = K Q^T : two 32-key blocks, their accumulation chains interleaved.  All 16
-    // operand reads are issued up front so the MFMAs stream behind the LDS instead of waiting
-    // for it pair by pair. ----
-    u32x4 kop[16];
+  f32x16 s[2];               // S^T of the tile whose softmax is being taken: two 32-key blocks
+  u32x4 pb[4];               // P^T of the previous tile, packed as the B operands of its four k-steps
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      kop[2 * ks] = *reinterpret_cast<const u32x4*>(cur + ka[ks]);
-      kop[2 * ks + 1] = *reinterpret_cast<const u32x4*>(cur + ka[ks] + 8192);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    f32x16 s[2];
+  for (int g = 0; g < 4; ++g) pb[g] = mk4(0u, 0u, 0u, 0u);
+
+  auto s_product = [&](const char* kt_tile, f32x16 (&out)[2]) {   // all 16 MFMAs of S^T = K Q^T, not interleaved
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+      for (int i = 0; i < 16; ++i) out[kb][i] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      s[0] = mfma32(kop[2 * ks], qreg[ks], s[0]);
-      s[1] = mfma32(kop[2 * ks + 1], qreg[ks], s[1]);
+      out[0] = mfma32(*reinterpret_cast<const u32x4*>(kt_tile + ka[ks]), qreg[ks], out[0]);
+      out[1] = mfma32(*reinterpret_cast<const u32x4*>(kt_tile + ka[ks] + 8192), qreg[ks], out[1]);
     }
-    // V^T operands for the second product: issued now, they land while the softmax runs
-    u32x4 vop[16];
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-      for (int db = 0; db < 4; ++db) vop[g * 4 + db] = *reinterpret_cast<const u32x4*>(cur + va[g ^ db] + db * 4096);
-    __builtin_amdgcn_sched_barrier(0);
+  };
 
+  if (any_tile) {
+    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0), lgkmcnt(0): the first tiles have landed, the zeros are written
+    lds_barrier();
+    s_product(kslot0, s);
+  }
+
+  // One iteration: tile t, with V(t-1) in v_prev, K(t+1) in k_next; K(t+3) goes where K(t) was,
+  // V(t+1) where V(t-2) was.
+  auto iteration = [&](int t, const char* vt, const char* ktile, char* k_refill, char* v_refill) {
+    // Own copies of every group but the newest have landed; after the barrier everybody's have,
+    // and everybody is done with the slots about to be refilled.  Every iteration issues one
+    // whole group (past the end it fetches the last tile again, into slots nobody reads any
+    // more), so the wait is the same constant everywhere.
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * kCopies));
+    lds_barrier();
+    fetch(kc, kbase, k_refill);
+    fetch(vc, vbase, v_refill);
+
+    const int k0 = t * kBN;
     // ---- mask (only tiles that cut an interval boundary) ----
     if (k0 < w_lo_max || k0 + kBN - 1 > w_hi_min) {
 #pragma unroll
@@ -164,56 +210,143 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
           if (key < lo || key > hi) s[kb][i] = -INFINITY;
         }
     }
+    __builtin_amdgcn_sched_barrier(0);
 
-    // ---- online softmax along keys ----
-    float mx = s[0][0];
+    // Each step below is one MFMA with the reads that feed the MFMA four steps later and its share
+    // of the vector work; MMSP_STEP_END pins the values so that neither the optimiser nor the
+    // instruction scheduler moves work from one step to another.
+#define MMSP_PIN(x) asm volatile("" : "+v"(x))
+#define MMSP_STEP_END() __builtin_amdgcn_sched_barrier(0)
+
+    // ================= phase 1: O^T += V(t-1)^T P(t-1)^T  beside  max(t) and the first exponentials of tile t =================
+    // (the first iteration multiplies an all-zero P with a slot of zeros)
+    float alpha = 1.f;
+    bool moved = false;
+    uint32_t w[16];          // P^T of tile t, two keys per word
+    float ps[4] = {0.f, 0.f, 0.f, 0.f};                 // fp32 sums of the unrounded P (LSE needs 1e-3)
+    float mx = -INFINITY, mx_other = -INFINITY;
+    auto exp_item = [&](int j) {                        // keys 2j, 2j+1 of the lane's 32
+      const f32x16& sv = s[j >> 3];
+      const int e = (j & 7) * 2;
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(sv[e], c, neg_mc));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(sv[e + 1], c, neg_mc));
+      ps[e & 3] += p0;
+      ps[(e + 1) & 3] += p1;
+      w[j] = pack2(p0, p1);
+      MMSP_PIN(ps[e & 3]); MMSP_PIN(ps[(e + 1) & 3]); MMSP_PIN(w[j]);
+    };
+    {
+      u32x2 vq[4][2];        // transposing reads in flight, four steps deep
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int i = 0; i < 4; ++i) {
+        vq[i][0] = lds_read_tr(vt + va[i & 3][0] + (i >> 2) * 4096);
+        vq[i][1] = lds_read_tr(vt + va[i & 3][1] + (i >> 2) * 4096);
+      }
+      MMSP_STEP_END();
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    if (__any(mx > m_ref + lazy_raw)) {                 // rare after the first tiles
-      const float m_new = fmaxf(m_ref, mx);
-      const float alpha = m_new == m_ref ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * c);   // -inf -> 0
-      m_ref = m_new;
-      neg_mc = m_new == -INFINITY ? 0.f : -m_new * c;
-      l *= alpha;
+      for (int i = 0; i < 16; ++i) {
+        const int g = i >> 2, db = i & 3;
+        const u32x4 vop = mk4(vq[i & 3][0].x, vq[i & 3][0].y, vq[i & 3][1].x, vq[i & 3][1].y);
+        oacc[db] = mfma32(vop, pb[g], oacc[db]);
+        if (i + 4 < 16) {
+          vq[i & 3][0] = lds_read_tr(vt + va[db][0] + (g + 1) * 4096);
+          vq[i & 3][1] = lds_read_tr(vt + va[db][1] + (g + 1) * 4096);
+        }
+        if (i < 5) {                                    // running maximum: 32 scores in 16 three-input maxima
+          const f32x16& sv = s[i >= 3 ? 1 : 0];
+          if (i == 0) { mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]); mx = fmaxf(fmaxf(mx, sv[3]), sv[4]); mx = fmaxf(fmaxf(mx, sv[5]), sv[6]); }
+          if (i == 1) { mx = fmaxf(fmaxf(mx, sv[7]), sv[8]); mx = fmaxf(fmaxf(mx, sv[9]), sv[10]); mx = fmaxf(fmaxf(mx, sv[11]), sv[12]); }
+          if (i == 2) { mx = fmaxf(fmaxf(mx, sv[13]), sv[14]); mx = fmaxf(fmaxf(mx, sv[15]), s[1][0]); mx = fmaxf(fmaxf(mx, s[1][1]), s[1][2]); }
+          if (i == 3) { mx = fmaxf(fmaxf(mx, sv[3]), sv[4]); mx = fmaxf(fmaxf(mx, sv[5]), sv[6]); mx = fmaxf(fmaxf(mx, sv[7]), sv[8]); }
+          if (i == 4) { mx = fmaxf(fmaxf(mx, sv[9]), sv[10]); mx = fmaxf(fmaxf(mx, sv[11]), sv[12]); mx = fmaxf(fmaxf(mx, sv[13]), sv[14]);
+                        mx = fmaxf(mx, sv[15]); mx_other = __shfl_xor(mx, 32); }
+          MMSP_PIN(mx);
+        }
+        if (i == 6) {                                   // lazily followed reference (branch-free; only the O rescale is conditional)
+          mx = fmaxf(mx, mx_other);
+          moved = mx > m_ref + lazy_raw;
+          const float m_new = moved ? mx : m_ref;
+          alpha = moved ? __builtin_amdgcn_exp2f((m_ref - m_new) * c) : 1.f;   // m_ref = -inf -> 0
+          m_ref = m_new;
+          neg_mc = m_new == -INFINITY ? 0.f : -m_new * c;
+          l *= alpha;
+          MMSP_PIN(neg_mc); MMSP_PIN(alpha); MMSP_PIN(l);
+        }
+        if (i >= 8) {                                   // exponentials of keys 0..15 of the lane
+          exp_item(i - 8);
+        }
+        MMSP_PIN(oacc[db]);
+        MMSP_STEP_END();
+      }
+    }
+    if (__any(moved)) {                                 // rare after the first tiles
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
     }
-    u32x4 pb[4];
-    float ps[4] = {0.f, 0.f, 0.f, 0.f};                 // fp32 sums of the unrounded P (LSE needs 1e-3)
+    MMSP_STEP_END();
+
+    // ================= phase 2: S^T of tile t+1  beside  the remaining exponentials of tile t =================
+    // (after the last tile the product runs on whatever the slot holds and is never used)
+    f32x16 sn[2];
+    {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      uint32_t w[8];
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][2 * j], c, neg_mc));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][2 * j + 1], c, neg_mc));
-        ps[(2 * j) & 3] += p0;
-        ps[(2 * j + 1) & 3] += p1;
-        w[j] = pack2(p0, p1);
+        for (int i = 0; i < 16; ++i) sn[kb][i] = 0.f;
+      u32x4 kq[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) kq[i] = *reinterpret_cast<const u32x4*>(ktile + ka[i >> 1] + (i & 1) * 8192);
+      MMSP_STEP_END();
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int ks = i >> 1, kb = i & 1;
+        sn[kb] = mfma32(kq[i & 3], qreg[ks], sn[kb]);
+        if (i + 4 < 16) kq[i & 3] = *reinterpret_cast<const u32x4*>(ktile + ka[ks + 2] + kb * 8192);
+        if (i < 8) exp_item(8 + i);
+        MMSP_PIN(sn[kb]);
+        MMSP_STEP_END();
       }
-      pb[kb * 2 + 0] = mk4(w[0], w[1], w[2], w[3]);
-      pb[kb * 2 + 1] = mk4(w[4], w[5], w[6], w[7]);
+      l += (ps[0] + ps[1]) + (ps[2] + ps[3]);
     }
-    l += (ps[0] + ps[1]) + (ps[2] + ps[3]);
-
-    // ---- O^T += V^T P^T ----
+    MMSP_STEP_END();
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-        oacc[db] = mfma32(vop[g * 4 + db], pb[g], oacc[db]);
+    for (int g = 0; g < 4; ++g) pb[g] = mk4(w[4 * g], w[4 * g + 1], w[4 * g + 2], w[4 * g + 3]);
+    s[0] = sn[0];
+    s[1] = sn[1];
   };
+#undef MMSP_PIN
+#undef MMSP_STEP_END
 
-  // Three bodies per trip so that every LDS offset is an immediate.
-  for (int kt = kt0; kt <= kt1; kt += 3) {
-    tile_body(kt, stage0, stage2);
-    if (kt + 1 <= kt1) tile_body(kt + 1, stage1, stage0);
-    if (kt + 2 <= kt1) tile_body(kt + 2, stage2, stage1);
+  int t = kt0;
+  for (; t + 2 <= kt1; t += 3) {
+    iteration(t, vslot2, kslot1, kslot0, vslot1);
+    iteration(t + 1, vslot0, kslot2, kslot1, vslot2);
+    iteration(t + 2, vslot1, kslot0, kslot2, vslot0);
+  }
+  if (t <= kt1) {
+    iteration(t, vslot2, kslot1, kslot0, vslot1);
+    if (t + 1 <= kt1) iteration(t + 1, vslot0, kslot2, kslot1, vslot2);
+  }
+
+  if (any_tile) {            // O^T += V^T P^T of the last tile
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    lds_barrier();
+    auto last_product = [&](const char* vt) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          const u32x2 v0 = lds_read_tr(vt + va[db][0] + g * 4096);
+          const u32x2 v1 = lds_read_tr(vt + va[db][1] + g * 4096);
+          oacc[db] = mfma32(mk4(v0.x, v0.y, v1.x, v1.y), pb[g], oacc[db]);
+        }
+    };
+    const int last_slot = (kt1 - kt0) % kSlots;
+    if (last_slot == 0) last_product(vslot0);
+    else if (last_slot == 1) last_product(vslot1);
+    else last_product(vslot2);
   }
   const float m = m_ref;
 
@@ -256,12 +389,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
 
 }  // namespace
 
-int64_t fwd_bf16_workspace_bytes(int Hkv, int64_t n_k) { return (int64_t)Hkv * tiles_of(n_k) * kImageBytes; }
-
 hipError_t launch_fwd_bf16(const StepArgs& a, hipStream_t stream) {
-  // V^T tile images of the visiting block
-  hipError_t e = launch_transpose_tiles(a.v, a.kv_ts, a.kv_hs, a.Hkv, a.k_row0, a.n_k, a.ws, stream);
-  if (e != hipSuccess) return e;
   const int n_qt = (a.n_q + kBM - 1) / kBM;
   int xcd_per_kv = 0, n_blocks = n_qt * a.Hq;
   if (8 % a.Hkv == 0) {

@@ -1,5 +1,5 @@
 // Building blocks shared by the bf16 matrix-core kernels: vector types, the 32x32x16 MFMA
-// wrapper, and the two LDS tile layouts with their global->LDS staging.
+// wrapper, and the LDS tile layout with its global->LDS staging.
 //
 // MFMA v_mfma_f32_32x32x16_bf16 (one wavefront, C[32x32] += A[32x16] * B[16x32]):
 //   A operand: lane L holds row (L % 32), k = (L / 32) * 8 .. +8      (8 consecutive k)
@@ -10,8 +10,9 @@
 // a lane, and so that C's register layout can be fed back as a B operand: for MFMA k-slot
 // (half = L / 32, j = 0..7) of the k-step that consumes C registers 8t..8t+7, the row index is
 //   16 t + (j / 4) * 8 + half * 4 + (j % 4).
-// The other operand of that second product (V^T, K^T, Q^T, dO^T) is staged in LDS in exactly
-// this permuted order ("TileT"), so the sum over k pairs matching rows.
+// The other operand of that second product (V^T, K^T, Q^T, dO^T) is read from the natural-
+// orientation tile in LDS by transposing reads that deliver exactly this permuted order (see
+// TileS below), so the sum over k pairs matching rows.
 #pragma once
 #include "common.h"
 
@@ -38,76 +39,7 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
-// ---------------------------------------------------------------------------------------
-// TileN: a [64 rows][128 cols] bf16 tile in its natural orientation (row = token, col = d),
-// 256 bytes per row, 16-byte chunks XOR-swizzled by (row & 15) so that the 16 lanes of a
-// ds_read_b128 phase, which read the same chunk of 16 consecutive rows, hit distinct banks.
-// Used as an MFMA A operand whose k index runs along d.
-// ---------------------------------------------------------------------------------------
-constexpr int kTileBytes = 64 * 128 * 2;     // 16 KiB, both layouts
-
-__device__ __forceinline__ int tile_n_offset(int row, int chunk /*0..15*/) {
-  return row * 256 + ((chunk ^ (row & 15)) << 4);
-}
-
-// ---------------------------------------------------------------------------------------
-// TileT: the same 64x128 tile transposed, [128 d][64 token slots].  Token t of the tile sits
-// in slot (t & ~15) | swap_bits_2_3(t & 15), which is the k-slot order described above.
-// Rows 2j and 2j+1 share one 256-byte bank line; which half a row takes is flipped by bit 3
-// of d, and the 16-byte chunks inside the half are XOR-swizzled by (d >> 4) ^ (d >> 1).  With
-// this placement both the b128 operand reads (32 consecutive d, one chunk) and the b64
-// transposing writes (d = 8 * lane + e, see tile_store_t) touch every bank equally often.
-// ---------------------------------------------------------------------------------------
-__device__ __forceinline__ int tile_t_offset(int d, int chunk /*0..7*/) {
-  return (d >> 1) * 256 + (((d ^ (d >> 3)) & 1) << 7) + (((chunk ^ (d >> 4) ^ (d >> 1)) & 7) << 4);
-}
-
-// Staging registers for one 64x128 tile and 256 threads: thread t owns the token group
-// kg = stage_kg(t) (tokens 4kg .. 4kg+3) and d-chunk (t%16)*8 .. +8  ->  four 16-byte global
-// loads, each row of the tile being read by 16 consecutive lanes (256 contiguous bytes).
-// Within a wavefront the 16-lane groups take token groups 0, 2, 1, 3 so that the first 32
-// lanes of a transposing b64 write differ in the 8-byte half of a chunk, not in the chunk.
-struct TileRegs { u32x4 r[4]; };
-
-__device__ __forceinline__ int stage_kg(int tid) {
-  return (tid >> 6) * 4 + ((tid >> 4) & 1) * 2 + ((tid >> 5) & 1);
-}
-
-// rows are clamped to [0, n_rows-1] so that every load is in bounds; clamped duplicates are
-// masked (or never stored) by the caller.
-__device__ __forceinline__ void tile_load(TileRegs& t, const uint16_t* base, int64_t row_stride, int row0, int n_rows,
-                                          int tid) {
-  const int tok = stage_kg(tid) * 4, dc = tid & 15;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int row = min(row0 + tok + r, n_rows - 1);
-    t.r[r] = *reinterpret_cast<const u32x4*>(base + (int64_t)row * row_stride + dc * 8);
-  }
-}
-
-__device__ __forceinline__ uint32_t comp(const u32x4& v, int i) { return v[i]; }   // i constant after unrolling
-
-__device__ __forceinline__ void tile_store_t(const TileRegs& t, char* tile, int tid) {
-  const int kg = stage_kg(tid), dc = tid & 15;
-  // tokens 4kg..4kg+3: 16-group g16 = kg/4, offset bits (b3,b2) = ((kg%4)>>1, (kg%4)&1);
-  // slot = b2*8 + b3*4 + (0..3)  ->  chunk = g16*2 + b2, byte offset inside the chunk = b3*8
-  const int chunk = (kg >> 2) * 2 + (kg & 1);
-  const int sub = ((kg >> 1) & 1) * 8;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int d = dc * 8 + e;
-    const int wi = e >> 1;
-    u32x2 out;
-    if (e & 1) {   // high halves
-      out.x = __builtin_amdgcn_perm(comp(t.r[1], wi), comp(t.r[0], wi), 0x07060302u);
-      out.y = __builtin_amdgcn_perm(comp(t.r[3], wi), comp(t.r[2], wi), 0x07060302u);
-    } else {       // low halves
-      out.x = __builtin_amdgcn_perm(comp(t.r[1], wi), comp(t.r[0], wi), 0x05040100u);
-      out.y = __builtin_amdgcn_perm(comp(t.r[3], wi), comp(t.r[2], wi), 0x05040100u);
-    }
-    *reinterpret_cast<u32x2*>(tile + tile_t_offset(d, chunk) + sub) = out;
-  }
-}
+constexpr int kTileBytes = 64 * 128 * 2;     // 16 KiB: one 64 x 128 bf16 tile
 
 // ---------------------------------------------------------------------------------------
 // Asynchronous global -> LDS copies (global_load_lds_dwordx4): every lane supplies its own
@@ -140,25 +72,11 @@ __device__ __forceinline__ void lds_barrier_after_write() {
   lds_barrier();
 }
 
-// TileN by DMA: the tile is 16 wavefront-copies of 4 rows; copy j of a wavefront lands rows
-// 4j .. 4j+3.  Lane l of copy j fetches logical chunk (l % 16) ^ (row & 15) of row 4j + l/16.
-// kCopies = 16 / (wavefronts sharing the tile); the wavefront with index w takes copies
-// w, w + W, ...  Offsets are bytes from the tile's first row and fit 32 bits.
+// A tile is 16 wavefront-copies of 4 rows; copy j lands rows 4j .. 4j+3.  kCopies = 16 /
+// (wavefronts sharing the tile); the wavefront with index w takes copies w, w + W, ...
+// Offsets are bytes from the tile's first row and fit 32 bits.
 template <int kCopies>
 struct DmaOffs { uint32_t o[kCopies]; };
-
-template <int kCopies>
-__device__ __forceinline__ DmaOffs<kCopies> dma_n_offsets(int64_t row_stride_elems, int rows_left, int wave, int lane) {
-  constexpr int W = 16 / kCopies;
-  DmaOffs<kCopies> t;
-#pragma unroll
-  for (int i = 0; i < kCopies; ++i) {
-    const int row = 4 * (wave + i * W) + (lane >> 4);
-    const int chunk = (lane & 15) ^ (row & 15);
-    t.o[i] = (uint32_t)(min(row, rows_left - 1) * (int)row_stride_elems * 2 + chunk * 16);
-  }
-  return t;
-}
 
 template <int kCopies>
 __device__ __forceinline__ void dma_tile_n(const char* tile_ptr /* uniform */, const DmaOffs<kCopies>& off, char* lds_tile,
@@ -168,12 +86,60 @@ __device__ __forceinline__ void dma_tile_n(const char* tile_ptr /* uniform */, c
   for (int i = 0; i < kCopies; ++i) dma16(tile_ptr + off.o[i], lds_tile + (wave + i * W) * 1024);
 }
 
-// A pre-built 16 KiB LDS image (see transpose_tiles) copied verbatim.
+// ---------------------------------------------------------------------------------------
+// TileS: a [64 rows][128 cols] bf16 tile in its natural orientation (row = token, col = d),
+// 256 bytes per row, the 16-byte chunk c of row r stored at chunk position c ^ swz16(r).
+// One copy in LDS serves both operand orientations:
+//   * k index along d (rows = MFMA rows): ds_read_b128 of chunk (2 ks + half) of row (lane % 32);
+//     the 16 lanes of a phase read one chunk of 16 consecutive rows, and swz16 is a bijection of
+//     r & 15, so they hit 16 distinct 16-byte bank groups;
+//   * k index along the tokens (rows of the MFMA operand = d): two ds_read_b64_tr_b16 per
+//     operand.  In each group of 16 lanes, lane a + 4 m supplies the address of 4 consecutive
+//     d (8 bytes) of token row m; the instruction hands lane l of the group the element d = l
+//     of the four rows m = 0..3.  The four rows of a read are 4 consecutive tokens, whose
+//     swz16 values differ in bits 2..3, i.e. they lie in four different 64-byte bank groups.
+// The k-slot order of the second kind follows the C layout of the first product (see the top
+// of this file): for the 16 tokens 16 g .. 16 g + 15 of a tile, the lanes of half h take
+// tokens 16 g + 4 h + {0..3} (first read) and 16 g + 8 + 4 h + {0..3} (second read).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int swz16(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+__device__ __forceinline__ int tile_s_offset(int row, int chunk /*0..15*/) {
+  return row * 256 + ((chunk ^ swz16(row & 15)) << 4);
+}
+
+typedef short s16x4 __attribute__((__vector_size__(4 * sizeof(short))));
+
+__device__ __forceinline__ u32x2 lds_read_tr(const char* p) {
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+  return __builtin_bit_cast(u32x2, v);
+}
+
+// Byte offset, inside a TileS tile, of the address this lane supplies to the transposing read
+// of d block db (32 rows of the operand), for tokens 4 h + m (sec = 0) or 8 + 4 h + m (sec = 1)
+// of token group 0; token group g adds g * 4096 bytes.
+__device__ __forceinline__ int tile_s_tr_offset(int lane, int db, int sec) {
+  const int grp = lane >> 4, a = lane & 3, m = (lane >> 2) & 3;      // lane = 16 grp + 4 m + a
+  const int h = grp >> 1, dsub = grp & 1;
+  const int row = sec * 8 + h * 4 + m;
+  const int chunk = db * 4 + dsub * 2 + (a >> 1);
+  return tile_s_offset(row, chunk) + (a & 1) * 8;
+}
+
+// TileS by asynchronous copies: lane l of copy j fetches the logical chunk that belongs at chunk
+// position l % 16 of row 4j + l / 16, i.e. chunk (l % 16) ^ swz16(row); rows past the end of the
+// tensor repeat the last row.
 template <int kCopies>
-__device__ __forceinline__ void dma_tile_image(const char* image /* uniform */, char* lds_tile, int wave, int lane) {
+__device__ __forceinline__ DmaOffs<kCopies> dma_s_offsets(int64_t row_stride_elems, int rows_left, int wave, int lane) {
   constexpr int W = 16 / kCopies;
+  DmaOffs<kCopies> t;
 #pragma unroll
-  for (int i = 0; i < kCopies; ++i) dma16(image + (wave + i * W) * 1024 + lane * 16, lds_tile + (wave + i * W) * 1024);
+  for (int i = 0; i < kCopies; ++i) {
+    const int row = 4 * (wave + i * W) + (lane >> 4);
+    const int chunk = (lane & 15) ^ swz16(row & 15);
+    t.o[i] = (uint32_t)(min(row, rows_left - 1) * (int)row_stride_elems * 2 + chunk * 16);
+  }
+  return t;
 }
 
 }  // namespace mmsp

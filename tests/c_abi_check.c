@@ -34,7 +34,7 @@ int main(int argc, char** argv) {
   memset(&shape, 0, sizeof shape);
   shape.n_q_heads = 28; shape.n_kv_heads = 4; shape.head_dim = 128; shape.io_dtype = MMSP_BF16; shape.softmax_scale = 0.0883883f;
   shape.q_tok_stride = 28 * 128; shape.q_head_stride = 128; shape.kv_tok_stride = 4 * 128; shape.kv_head_stride = 128; shape.lse_head_stride = 8192;
-  printf("ws %zu\n", p_mmsp_workspace_bytes(&shape, 8192, 8192, 0));
+  printf("ws %zu\n", p_mmsp_workspace_bytes(&shape, 8192, 8192, 1));
   mmsp_status st = p_mmsp_zigzag_layout(10, 4, 0, ids, l2g);
   printf("bad %d %s\n", (int)st, strlen(p_mmsp_last_error()) > 0 ? "message" : "empty");
   return 0;

@@ -189,16 +189,17 @@ def test_null_and_misaligned_pointers_are_rejected():
 
 def test_workspace_size_and_rejection():
     shape = _shape()
-    need = B.mmsp_workspace_bytes(shape, 200, 130, 0)
-    assert need >= 2 * 3 * 16384 and need % 16 == 0          # 2 KV heads x ceil(130/64) tiles of 16 KiB at least
+    assert B.mmsp_workspace_bytes(shape, 200, 130, 0) == 0    # the forward needs no scratch
+    need = B.mmsp_workspace_bytes(shape, 200, 130, 1)
+    # backward: two padded statistics rows per query head (4 heads x ceil(200/64) tiles x 64 floats each)
+    # plus the fixed area for partial dK / dV sums
+    assert need >= 2 * 4 * 4 * 64 * 4 and need % 16 == 0
     assert B.mmsp_workspace_bytes(_shape(io_dtype=B.MMSP_F32, head_dim=64), 200, 130, 1) == 0
     blk = B.make_block(0, 16, 0, 16, B.MMSP_MASK_FULL)
-    with pytest.raises(B.MmspError) as e:
-        B.mmsp_attn_step_fwd(shape, blk, FAKE, FAKE, FAKE, FAKE, FAKE, 0, None, 0)
-    assert e.value.status == B.MMSP_ERR_WORKSPACE_TOO_SMALL
-    with pytest.raises(B.MmspError) as e:
-        B.mmsp_attn_step_fwd(shape, blk, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 100)
-    assert e.value.status == B.MMSP_ERR_WORKSPACE_TOO_SMALL
+    for ws, nbytes in ((None, 0), (FAKE, 100)):
+        with pytest.raises(B.MmspError) as e:
+            B.mmsp_attn_step_bwd(shape, blk, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 0, ws, nbytes)
+        assert e.value.status == B.MMSP_ERR_WORKSPACE_TOO_SMALL
 
 
 def test_backward_checks_the_workspace_before_it_launches_anything():
@@ -242,5 +243,5 @@ def test_header_is_plain_c_and_usable_from_a_c_program(tmp_path):
     assert out[1] == "plan %d %d %d %d %d %d" % (src, blk.q_row0, blk.n_q, blk.k_row0, blk.n_k, blk.mask)
     sh = B.mmsp_2d_layout(262144, 4, 8, 13, 28, 4)
     assert out[2] == "2d %d %d %d %d %d %d %d" % (sh.head_rank, sh.ring_rank, sh.q_head0, sh.n_q_heads, sh.kv_head0, sh.n_kv_heads, sh.chunk_len)
-    assert out[3] == "ws %d" % (4 * 128 * 16384)
+    assert out[3] == "ws %d" % B.mmsp_workspace_bytes(B.make_shape(28, 4, 128, B.MMSP_BF16, 0.0883883, (28 * 128, 128), (4 * 128, 128), 8192), 8192, 8192, 1)
     assert out[4] == "bad %d message" % B.MMSP_ERR_INVALID_ARG

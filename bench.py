@@ -227,38 +227,16 @@ def main():
     ap.add_argument("--data-movement", action="store_true",
                     help="only time the HBM-bound sharding kernels at the 256K-token shapes (zigzag gather / scatter of Q, "
                          "head packing around the all-to-all) and print one JSON line with their GB/s")
-    ap.add_argument("--ceiling", action="store_true",
-                    help="only run the stand-alone matrix-core ceiling probe (what MFMA + LDS + softmax-like work sustains "
-                         "with trivial and with random operands) and print its lines")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="only run a plain 1 GiB device copy (scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the ring (one rank); this build has no multi-GPU path: "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    if args.ceiling:
-        import subprocess
-        probe = os.path.join(ROOT, "paper_2408_10188_amd", "ceiling_probe")
-        if not os.path.exists(probe):
-            print("ceiling_probe is not built: run __graft_entry__.build() first", file=sys.stderr)
-            sys.exit(1)
-        sys.exit(subprocess.run([probe]).returncode)
-
     import numpy as np
     import torch
     from paper_2408_10188_amd import binding as B
     from paper_2408_10188_amd import ring, synth
-
-    if args.copy_calibration:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")       # 1 GiB read + 1 GiB written per copy
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 3}))
-        return
 
     if args.data_movement:
         print(json.dumps(bench_data_movement(args, torch, B)))

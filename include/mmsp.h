@@ -236,6 +236,23 @@ mmsp_status mmsp_attn_step_bwd(const mmsp_shape* shape, const mmsp_block* blk,
                                float* dq_acc, float* dk, float* dv, int accumulate_dkdv,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* mmsp_attn_step_bwd for callers that cannot allocate device memory or pass a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * same kernels, with their scratch (padded row statistics, partial dK/dV sums) in a 72 MiB
+ * area built into the library's device image instead of a caller workspace.  Each GPU the
+ * library runs on holds that area until the process ends.  The call allocates and frees
+ * nothing.  A block whose scratch need exceeds the area (n_q_heads x n_q rows, padded to 64,
+ * above 1,048,576) is rejected with MMSP_ERR_WORKSPACE_TOO_SMALL before anything is enqueued.
+ * Nothing in the area has to start at zero and nothing in it outlives the call's kernels, but
+ * all calls on one GPU share it: calls that may overlap in time (different streams, or
+ * threads) race; keep them on one stream.  Arguments and results as mmsp_attn_step_bwd. */
+mmsp_status mmsp_attn_step_bwd_static(const mmsp_shape* shape, const mmsp_block* blk,
+                                      const void* q, const void* k, const void* v,
+                                      const void* o_final, const void* d_o,
+                                      const float* lse_final, float* delta, int compute_delta,
+                                      float* dq_acc, float* dk, float* dv, int accumulate_dkdv,
+                                      void* hip_stream);
+
 /* Message for the last non-OK status returned on the calling thread ("" if none). */
 const char* mmsp_last_error(void);
 

@@ -17,7 +17,7 @@ MMSP_MASK_FULL, MMSP_MASK_CAUSAL_DIAG, MMSP_MASK_NONE = 0, 1, 2
 MMSP_BF16, MMSP_F32 = 0, 1
 
 EXPORTS = ["mmsp_zigzag_layout", "mmsp_zigzag_plan", "mmsp_contiguous_plan", "mmsp_zigzag_plan_packed", "mmsp_2d_layout", "mmsp_workspace_bytes", "mmsp_attn_step_fwd",
-           "mmsp_attn_merge", "mmsp_attn_delta", "mmsp_attn_step_bwd", "mmsp_zigzag_gather", "mmsp_zigzag_scatter",
+           "mmsp_attn_merge", "mmsp_attn_delta", "mmsp_attn_step_bwd", "mmsp_attn_step_bwd_static", "mmsp_zigzag_gather", "mmsp_zigzag_scatter",
            "mmsp_a2a_pack_heads", "mmsp_a2a_unpack_heads", "mmsp_last_error"]
 
 
@@ -73,6 +73,8 @@ _lib.mmsp_attn_merge.argtypes = [ctypes.POINTER(MmspShape), _I64, _I64, _P, _P, 
 _lib.mmsp_attn_delta.argtypes = [ctypes.POINTER(MmspShape), _I64, _I64, _P, _P, _P, _P]
 _lib.mmsp_attn_step_bwd.argtypes = [ctypes.POINTER(MmspShape), ctypes.POINTER(MmspBlock), _P, _P, _P, _P, _P, _P, _P,
                                     _INT, _P, _P, _P, _INT, _P, _SZ, _P]
+_lib.mmsp_attn_step_bwd_static.argtypes = [ctypes.POINTER(MmspShape), ctypes.POINTER(MmspBlock), _P, _P, _P, _P, _P, _P,
+                                           _P, _INT, _P, _P, _P, _INT, _P]
 for _name in EXPORTS:
     if _name not in ("mmsp_last_error", "mmsp_workspace_bytes"):
         getattr(_lib, _name).restype = _INT
@@ -180,6 +182,13 @@ def mmsp_attn_merge(shape, row0, n_rows, o_acc, lse_acc, o_part, lse_part, o_fin
 def mmsp_attn_delta(shape, row0, n_rows, o_final, d_o, delta, stream=0):
     _check(_lib.mmsp_attn_delta(ctypes.byref(shape), row0, n_rows, _ptr(o_final), _ptr(d_o), _ptr(delta),
                                 stream or None))
+
+
+def mmsp_attn_step_bwd_static(shape, blk, q, k, v, o_final, d_o, lse_final, delta, compute_delta, dq_acc, dk, dv,
+                              accumulate_dkdv, stream=0):
+    _check(_lib.mmsp_attn_step_bwd_static(ctypes.byref(shape), ctypes.byref(blk), _ptr(q), _ptr(k), _ptr(v),
+                                          _ptr(o_final), _ptr(d_o), _ptr(lse_final), _ptr(delta), int(compute_delta),
+                                          _ptr(dq_acc), _ptr(dk), _ptr(dv), int(accumulate_dkdv), stream or None))
 
 
 def mmsp_attn_step_bwd(shape, blk, q, k, v, o_final, d_o, lse_final, delta, compute_delta, dq_acc, dk, dv,

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/mmsp.h"
 #include "common.h"
@@ -124,6 +125,32 @@ mmsp_status check_rows_copy(int64_t row_bytes, const void* a, const void* b) {
 }
 
 }  // namespace
+
+// Scratch of mmsp_attn_step_bwd_static: lives in the library's device image, so every GPU the
+// library runs on holds its own copy from load to process end.  Host code never uses the
+// array's name as an address (on the host it is only a handle for the symbol lookup): the
+// device address is asked for once per device and kept.
+constexpr size_t kStaticScratchBytes = 72u << 20;
+static __device__ __align__(256) char scratch[kStaticScratchBytes];
+
+static hipError_t static_scratch(char** out) {
+  static std::mutex mu;
+  static char* address_on_device[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (address_on_device[dev] == nullptr) {
+    char* ptr = nullptr;
+    e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));   // of the current device's copy
+    if (e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    address_on_device[dev] = ptr;
+  }
+  *out = address_on_device[dev];
+  return hipSuccess;
+}
 
 extern "C" {
 
@@ -383,6 +410,29 @@ mmsp_status mmsp_attn_step_bwd(const mmsp_shape* shape, const mmsp_block* blk, c
   a.dq = dq_acc; a.dk = dk; a.dv = dv; a.accumulate = accumulate_dkdv != 0;
   if (shape->io_dtype == MMSP_BF16) return device_result(mmsp::launch_bwd_bf16(a, stream), "step_bwd (bf16)");
   return device_result(mmsp::launch_bwd_f32(a, stream), "step_bwd (f32)");
+}
+
+mmsp_status mmsp_attn_step_bwd_static(const mmsp_shape* shape, const mmsp_block* blk, const void* q, const void* k,
+                                      const void* v, const void* o_final, const void* d_o, const float* lse_final,
+                                      float* delta, int compute_delta, float* dq_acc, float* dk, float* dv,
+                                      int accumulate_dkdv, void* hip_stream) {
+  mmsp_status st = check_shape(shape);
+  if (st != MMSP_OK) return st;
+  st = check_block(shape, blk);
+  if (st != MMSP_OK) return st;
+  const size_t need = shape->io_dtype == MMSP_BF16 ? needed_workspace(shape, blk->n_q, blk->n_k, true) : 0;
+  if (need > kStaticScratchBytes)
+    return fail(MMSP_ERR_WORKSPACE_TOO_SMALL,
+                "block of %lld query rows x %d heads needs %zu bytes of scratch, the built-in area holds %zu "
+                "(use mmsp_attn_step_bwd with a workspace)",
+                (long long)blk->n_q, shape->n_q_heads, need, kStaticScratchBytes);
+  char* ptr = nullptr;
+  if (need > 0) {
+    hipError_t e = static_scratch(&ptr);
+    if (e != hipSuccess) return device_result(e, "address of the built-in scratch");
+  }
+  return mmsp_attn_step_bwd(shape, blk, q, k, v, o_final, d_o, lse_final, delta, compute_delta, dq_acc, dk, dv,
+                            accumulate_dkdv, ptr, need > 0 ? kStaticScratchBytes : 0, hip_stream);
 }
 
 }  // extern "C"

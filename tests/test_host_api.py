@@ -245,3 +245,20 @@ def test_header_is_plain_c_and_usable_from_a_c_program(tmp_path):
     assert out[2] == "2d %d %d %d %d %d %d %d" % (sh.head_rank, sh.ring_rank, sh.q_head0, sh.n_q_heads, sh.kv_head0, sh.n_kv_heads, sh.chunk_len)
     assert out[3] == "ws %d" % B.mmsp_workspace_bytes(B.make_shape(28, 4, 128, B.MMSP_BF16, 0.0883883, (28 * 128, 128), (4 * 128, 128), 8192), 8192, 8192, 1)
     assert out[4] == "bad %d message" % B.MMSP_ERR_INVALID_ARG
+
+
+def test_static_backward_rejects_blocks_beyond_its_built_in_scratch():
+    """4 heads x 300000 rows of statistics exceed the 72 MiB area: refused on the host, with the
+    sizes in the message, before any device call (without a GPU one would give MMSP_ERR_DEVICE)."""
+    n = 300000
+    shape = _shape(lse_head_stride=n)
+    blk = B.make_block(0, n, 0, 64, B.MMSP_MASK_FULL)
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_step_bwd_static(shape, blk, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 0)
+    assert e.value.status == B.MMSP_ERR_WORKSPACE_TOO_SMALL
+    assert "built-in" in str(e.value) and str(72 << 20) in str(e.value)
+    # bad arguments are reported as such, as by mmsp_attn_step_bwd
+    with pytest.raises(B.MmspError) as e:
+        B.mmsp_attn_step_bwd_static(_shape(n_kv_heads=3), B.make_block(0, 16, 0, 16, B.MMSP_MASK_FULL), FAKE, FAKE, FAKE,
+                                    None, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 0)
+    assert e.value.status == B.MMSP_ERR_INVALID_ARG

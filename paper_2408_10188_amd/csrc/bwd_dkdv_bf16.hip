@@ -32,11 +32,6 @@ constexpr int kGroup = 2 * kCopies + 1;         // copies per wavefront and ring
 constexpr int kSlots = 4;
 constexpr int kDepth = 4;                        // LDS operand reads in flight ahead of the matrix instructions (power of two)
 
-__device__ __forceinline__ void dma4(const char* gptr, char* lds_wave_base) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
-                                   (__attribute__((address_space(3))) void*)lds_wave_base, 4, 0, 0);
-}
-
 #define MMSP_PIN(x) asm volatile("" : "+v"(x))
 #define MMSP_PIN_ACC(x) asm volatile("" : "+a"(x))     // keeps an accumulator in the AGPR half of the register file
 #define MMSP_STEP_END() __builtin_amdgcn_sched_barrier(0)

@@ -47,9 +47,25 @@ constexpr int kTileBytes = 64 * 128 * 2;     // 16 KiB: one 64 x 128 bf16 tile
 // address.  Completion is tracked by vmcnt.  A swizzled LDS layout is obtained by permuting
 // which global chunk each lane fetches.
 // ---------------------------------------------------------------------------------------
+// The copy is written as inline assembly, not through the compiler's builtin, on purpose.  The
+// compiler's wait-count pass treats a global->LDS copy it knows about as an access to both
+// memories: while one is in flight it turns every wait for an LDS read into "wait for all LDS
+// reads", which defeats reading operands several matrix instructions ahead, and it adds waits
+// on the copy counter wherever it cannot tell an LDS read from a copy's target.  The pipelines
+// here wait for their copies explicitly (s_waitcnt vmcnt(n) + barrier), so the compiler need
+// not know.  A copy it does not count can only make its own vmcnt waits stricter than needed
+// (the counter retires in order), never too weak.  M0 (the copy's LDS base) is a register the
+// compiler reserves and sets itself right before each of its own uses; nothing else in these
+// kernels uses it.
 __device__ __forceinline__ void dma16(const char* gptr, char* lds_wave_base) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr,
-                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+  const uint32_t lds = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_wave_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void dma4(const char* gptr, char* lds_wave_base) {   // 4 bytes per lane
+  const uint32_t lds = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_wave_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds), "v"(gptr) : "memory");
 }
 
 // Bare workgroup barrier for the asynchronous-copy pipelines.  __syncthreads() (and any

@@ -76,18 +76,26 @@ class RankProblem:
             side = ring.SideLane(torch.cuda.Stream(), nans_like(o_acc), nans_like(lse), torch.empty_like(ws), ws_bytes)
         ring.rank_forward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, o_acc, lse, o_final,
                           fused_merge=fused_merge, o_part=o_part, lse_part=lse_part, ws=ws, ws_bytes=ws_bytes, side=side)
-        out = dict(o_acc=o_acc, lse=lse, o_final=o_final)
+        out = dict(o_acc=o_acc, lse=lse, o_final=o_final, _ctx=(shape, rank, qd, ws, ws_bytes, side))
         if do is not None:
-            dod = to_dev(do, self.bf16)
-            delta = nans_like(lse)
-            dq = torch.zeros_like(o_acc)
-            dk = torch.zeros(self.N, n, self.Hkv, self.d, dtype=torch.float32, device=DEV)
-            dv = torch.zeros_like(dk)
-            ring.rank_backward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, o_final, dod, lse, delta, dq, dk, dv,
-                               ws=ws, ws_bytes=ws_bytes, side=side)
-            out.update(delta=delta, dq=dq, dk_zz=dk, dv_zz=dv)
+            out.update(self.run_backward(out, do))
         torch.cuda.synchronize()
         return out
+
+    def run_backward(self, fwd, do):
+        """Backward of the rank whose forward results are in `fwd` (from run_gpu) for the output
+        gradient `do`, in the same launch configuration; returns fresh delta / dq / dk_zz / dv_zz."""
+        shape, rank, qd, ws, ws_bytes, side = fwd["_ctx"]
+        n = 2 * self.C
+        dod = to_dev(do, self.bf16)
+        delta = nans_like(fwd["lse"])
+        dq = torch.zeros_like(fwd["o_acc"])
+        dk = torch.zeros(self.N, n, self.Hkv, self.d, dtype=torch.float32, device=DEV)
+        dv = torch.zeros_like(dk)
+        ring.rank_backward(shape, self.T, self.N, rank, qd, self.k_zz, self.v_zz, fwd["o_final"], dod, fwd["lse"], delta,
+                           dq, dk, dv, ws=ws, ws_bytes=ws_bytes, side=side)
+        torch.cuda.synchronize()
+        return dict(delta=delta, dq=dq, dk_zz=dk, dv_zz=dv)
 
     def unzigzag(self, x_zz):
         """[N, 2C, ...] in zigzag order -> [T, ...] in sequence order (host numpy)."""

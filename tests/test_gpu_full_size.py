@@ -1,7 +1,7 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times: outputs
-the oracle can compute one by one (sampled query rows: O, LSE, dQ; sampled key rows: dK, dV at
-the 65K configuration) and properties that hold at any size (column sums of the rank's dK/dV
-contribution).  The sampled values come from the same oracle code as the small tests; there is
+the oracle can compute one by one (sampled query rows: O, LSE, dQ; sampled key rows: dK, dV; one
+whole document of the packed sequence) and properties that hold at any size (column sums of the
+rank's dK/dV contribution).  The sampled values come from the same oracle code as the small tests; there is
 no independent pin at these sizes."""
 import math
 
@@ -88,12 +88,66 @@ def test_config3_fwd_bwd_sampled_rows_and_keys(rank):
     assert max(errs) <= 2e-2, errs
 
 
+def _check_sampled_keys(prob, rank, out, q, do, rows, keys, what):
+    """dK / dV of the key rows `keys`, element by element, when `rows` are the only local query
+    rows that contribute to them: oracle forward of those rows over the whole sequence (all
+    heads; LSE and delta), then P and dS against the sampled keys."""
+    _, l2g = orc.zigzag_layout(prob.T, prob.N, rank)
+    K, V = prob.K_full().astype(np.float64), prob.V_full().astype(np.float64)
+    qr, dor = q[rows].astype(np.float64), do[rows].astype(np.float64)
+    O, LSE = orc.causal_attention(qr, K, V, prob.scale, q_pos=l2g[rows], row_block=16)
+    D = orc.delta(dor, O)
+    vis = orc.visible(l2g[rows], keys)
+    _, dk_ref, dv_ref = orc.attention_bwd(qr, K[keys], V[keys], dor, vis, prob.scale, LSE=LSE, D=D)
+    kidx = torch.from_numpy(_zigzag_index(prob, keys)).to(DEV)
+    dk = to_host64(out["dk_zz"].reshape(-1, prob.Hkv, prob.d)[kidx])
+    dv = to_host64(out["dv_zz"].reshape(-1, prob.Hkv, prob.d)[kidx])
+    errs = (max_abs(dk, dk_ref), max_abs(dv, dv_ref))
+    print(f"{what}: sampled-key errors (dK, dV) {errs}; max |dK| {np.abs(dk_ref).max():.3g}, max |dV| {np.abs(dv_ref).max():.3g}",
+          flush=True)
+    assert max(errs) <= 2e-2, errs
+    # With 262144 keys per row a single P is about 1e-5 and these gradients are far below the absolute
+    # bound, so it alone would pass an all-zero answer: also bound the error relative to the largest
+    # reference value (bf16 rounding of P and dS: 2^-9 per term).
+    assert errs[0] <= 3e-2 * np.abs(dk_ref).max() and errs[1] <= 3e-2 * np.abs(dv_ref).max(), errs
+
+
+def _zigzag_index(prob, pos):
+    """Flat row of dk_zz / dv_zz ([N, 2C, ...] in zigzag order) that holds sequence position pos."""
+    pos = np.asarray(pos, dtype=np.int64)
+    chunk, off = pos // prob.C, pos % prob.C
+    owner = np.where(chunk < prob.N, chunk, 2 * prob.N - 1 - chunk)
+    return owner * (2 * prob.C) + np.where(chunk < prob.N, 0, prob.C) + off
+
+
 def test_long_shard_fwd_bwd_sampled_rows():
     prob = RankProblem(synth.CONFIGS["long"])
+    T, C = prob.T, prob.C
     q, do = prob.rank_inputs(0)
     out = prob.run_gpu(0, q, do, two_streams=True)             # the launch configuration bench.py times
     _check_sampled_rows(prob, 0, out, q, do, _sample_rows(prob.C, 4, 300), backward=True)
     _check_column_sums(prob, out, do)
+    # dK / dV element by element.  (1) The run above, keys among the last 41 positions of the
+    # sequence: only the rank's last 41 rows see them, so their forward is all the oracle needs.
+    last = np.arange(2 * C - 41, 2 * C)
+    _check_sampled_keys(prob, 0, out, q, do, last, T - 1 - np.array([40, 17, 5, 1, 0]), "dense dO, keys at the end")
+    # (2) Keys anywhere (first chunk, chunk edges, other ranks' blocks, last chunk): every row of the
+    # second chunk sees them, and the oracle forward of 4096 rows x 28 heads x 262144 keys takes
+    # minutes.  A second backward whose dO is zero outside 40 sampled rows (spread over both chunks
+    # and over the 256-row tiles) runs the same launches on the same shapes, and rows with dO = 0
+    # contribute exactly nothing (dP = delta = 0), so those 40 rows are the whole answer.
+    rows = np.unique(np.concatenate([_sample_rows(C, 18, 301), [C - 1, C, 255, 256, 2 * C - 257]]))
+    do_sparse = np.zeros_like(do)
+    do_sparse[rows] = do[rows]
+    out2 = prob.run_backward(out, do_sparse)
+    keys = np.unique(np.concatenate([np.random.default_rng(8).choice(T, 24, replace=False),
+                                     [0, C - 1, C, 17 * C + 5, T - C - 1, T - C, T - 1]]))
+    _check_sampled_keys(prob, 0, out2, q, do_sparse, rows, keys, "dO on 40 rows, keys anywhere")
+    # rows with dO = 0 get dQ = 0 exactly; the sampled ones match the dense run's oracle values
+    dq2 = to_host64(out2["dq"])
+    mask = np.ones(2 * C, dtype=bool)
+    mask[rows] = False
+    assert np.all(dq2[mask] == 0)
 
 
 def test_ulysses_packed_fwd_bwd_sampled_rows():
@@ -130,6 +184,18 @@ def test_ulysses_packed_fwd_bwd_sampled_rows():
                 dq=max_abs(to_host64(dq[idx]), ref[2]))
     print("ulysses sampled-row errors", errs, flush=True)
     assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 and errs["dq"] <= 2e-2, errs
+    # dK / dV of one whole document, element by element: the shortest one that is complete (the
+    # last one may be truncated); its rows see only its own keys, so the oracle problem is the
+    # document by itself
+    lens = np.diff(cu)[:-1]
+    i = int(np.argmin(lens))
+    a, b = int(cu[i]), int(cu[i + 1])
+    qd64, kd64, vd64, dod64 = (x[a:b].astype(np.float64) for x in (q, k, v, do))
+    ref_doc = orc.causal_attention(qd64, kd64, vd64, scale, dO=dod64, row_block=1024)
+    doc_errs = dict(dk=max_abs(to_host64(dk[a:b]), ref_doc[3]), dv=max_abs(to_host64(dv[a:b]), ref_doc[4]),
+                    dq=max_abs(to_host64(dq[a:b]), ref_doc[2]), o=max_abs(to_host64(o_acc[a:b]), ref_doc[0]))
+    print(f"ulysses document {i} (rows {a}..{b}, {b - a} tokens): errors {doc_errs}", flush=True)
+    assert max(doc_errs.values()) <= 2e-2, doc_errs
     # per document: sum_j dV[j] = sum over heads and rows of the document of dO
     dvh = to_host64(dv)
     for a, b in zip(cu[:-1], cu[1:]):

@@ -187,6 +187,29 @@ def test_step_with_packed_documents(io_bf16, mask):
               dict(q_row0=50, n_q=300, k_row0=20, n_k=450, mask=mask, q_pos0=250, k_pos0=80), cu=cu, seed=32)
 
 
+@pytest.mark.parametrize("n_k,n_q,documents", [
+    (4261, 200, True),      # 34 key tiles x 8 KV heads = 272 workgroups: no cut, direct store (and its read-modify-write)
+    (4224, 64, False),      # the same with whole tiles and one query tile
+    (2811, 131, True),      # 22 key tiles -> query ranges cut in 2
+    (2048, 200, False),     # 16 -> 4
+    (1153, 77, True),       # 10 -> 6
+    (1100, 200, True),      # 9 -> 7
+])
+def test_dkdv_with_and_without_cut_query_ranges(n_k, n_q, documents):
+    """Many KV heads and a long key block with few query rows: the dK/dV kernel then runs one
+    workgroup per key tile (storing its result directly, adding to dk/dv in place when asked to
+    accumulate) or cuts the query range in 2..7 partial sums.  Causal mask with the block's rows
+    near the end of the key range, with and without document boundaries; _run_step checks dK, dV
+    (and dQ) element by element against the oracle for accumulate 0 and then 1."""
+    q_pos0 = n_k - n_q // 2                     # the diagonal crosses the last key tiles; the last rows see every key
+    cu = [0, 700, 701, n_k - 30, n_k + n_q] if documents else None   # the block's rows straddle the last boundary
+    _run_step(True, 8, 8, 128, n_q, n_k, dict(q_row0=0, n_q=n_q, k_row0=0, n_k=n_k, mask=B.MMSP_MASK_CAUSAL_DIAG,
+                                              q_pos0=q_pos0, k_pos0=0), cu=cu, seed=60 + n_q)
+    if not documents:                           # every pair visible: the variant without masking
+        _run_step(True, 8, 8, 128, n_q, n_k, dict(q_row0=0, n_q=n_q, k_row0=0, n_k=n_k, mask=B.MMSP_MASK_FULL),
+                  seed=61 + n_q)
+
+
 def test_merge_and_cast_kernel():
     rng = np.random.default_rng(40)
     n, H, d = 70, 3, 128

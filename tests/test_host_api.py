@@ -262,3 +262,26 @@ def test_static_backward_rejects_blocks_beyond_its_built_in_scratch():
         B.mmsp_attn_step_bwd_static(_shape(n_kv_heads=3), B.make_block(0, 16, 0, 16, B.MMSP_MASK_FULL), FAKE, FAKE, FAKE,
                                     None, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, 0)
     assert e.value.status == B.MMSP_ERR_INVALID_ARG
+
+
+def test_flop_convention_against_the_papers_complexity_table():
+    """The benchmark's forward count for a whole causal sequence is twice the appendix table's
+    attention entry (the table counts one operation per multiply-accumulate), apart from the
+    diagonal's T / 2 pairs; a factor-of-two slip either way fails here."""
+    import os
+    from paper_2408_10188_amd import accounting as acc
+    path = os.path.join(os.path.dirname(__file__), "golden", "attention_flops_table.txt")
+    rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 10
+    for _, T, L, H, d, printed in rows:
+        T, L, H, d, printed = int(T), int(L), int(H), int(d), float(printed)
+        # the printed entries follow T^2 d H L to within 2e-4 (and two decimals)
+        assert abs(acc.paper_table_tflops(T, d, H, L) - printed) <= 0.006 + 3e-4 * printed
+        ours = L * acc.attention_flops(acc.causal_pairs(T), d, H, forward=True, backward=False) / 1e12
+        assert abs(ours / (2 * printed) - 1) <= 1.0 / T + 0.006 / printed + 3e-4      # diagonal, print rounding
+    # backward = 2.5 x forward; the zigzag ranks' pairs add up to the whole causal triangle
+    assert acc.attention_flops(7, 128, 28, False, True) * 2 == acc.attention_flops(7, 128, 28, True, False) * 5
+    for N, C in ((4, 2048), (8, 4096), (32, 4096)):
+        assert N * acc.zigzag_pairs_of_rank(N, C) == acc.causal_pairs(2 * N * C)
+        assert sum(acc.contiguous_pairs_of_rank(N, C, r) for r in range(N)) == acc.causal_pairs(2 * N * C)
+    assert acc.packed_pairs([3, 1]) == 7

@@ -107,6 +107,12 @@ class RankProblem:
         return out.reshape(self.T, *x_zz.shape[2:])
 
 
+# The bounds the task fixes for the five named configurations (max absolute error against the
+# fp64 oracle).  Tests of those configurations apply exactly these; any test that scales a bound
+# (harder synthetic inputs, derived quantities) says so where it does and is not one of the five.
+NORTH_STAR_TOL = {"bf16": dict(o=2e-2, lse=1e-3, g=2e-2), "f32": dict(o=1e-5, lse=1e-5, g=1e-5)}
+
+
 def max_abs(a, b):
     """Largest |a - b|.  Infinities of the same sign in the same place count as equal (LSE of a row
     that sees nothing is -inf on both sides); a NaN on either side, or an infinity facing anything

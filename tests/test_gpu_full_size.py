@@ -12,9 +12,13 @@ import torch
 from oracle import mmsp_oracle as orc
 from paper_2408_10188_amd import binding as B
 from paper_2408_10188_amd import ring, synth
-from tests.helpers import DEV, RankProblem, max_abs, nans, nans_like, to_dev, to_host64
+from tests.helpers import DEV, NORTH_STAR_TOL, RankProblem, max_abs, nans, nans_like, to_dev, to_host64
 
 pytestmark = pytest.mark.gpu
+
+# configurations 2-5 are bf16: the absolute bounds the task fixes, unscaled
+TOL = NORTH_STAR_TOL["bf16"]
+assert TOL == dict(o=2e-2, lse=1e-3, g=2e-2)
 
 
 def _sample_rows(C, per_chunk, seed):
@@ -36,7 +40,7 @@ def _check_sampled_rows(prob, rank, out, q, do, rows, backward):
     if backward:
         errs["dq"] = max_abs(to_host64(out["dq"][idx]), ref[2])
     print(f"rank {rank}: sampled-row errors {errs}", flush=True)
-    assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 and errs.get("dq", 0) <= 2e-2, errs
+    assert errs["o"] <= TOL["o"] and errs["lse"] <= TOL["lse"] and errs.get("dq", 0) <= TOL["g"], errs
 
 
 def _check_column_sums(prob, out, do):
@@ -85,7 +89,7 @@ def test_config3_fwd_bwd_sampled_rows_and_keys(rank):
     dv = prob.unzigzag(to_host64(out["dv_zz"]))[keys, kvh:kvh + 1]
     errs = (max_abs(dk, dk_ref), max_abs(dv, dv_ref))
     print("sampled-key errors (dK, dV):", errs, flush=True)
-    assert max(errs) <= 2e-2, errs
+    assert max(errs) <= TOL["g"], errs
 
 
 def _check_sampled_keys(prob, rank, out, q, do, rows, keys, what):
@@ -105,7 +109,7 @@ def _check_sampled_keys(prob, rank, out, q, do, rows, keys, what):
     errs = (max_abs(dk, dk_ref), max_abs(dv, dv_ref))
     print(f"{what}: sampled-key errors (dK, dV) {errs}; max |dK| {np.abs(dk_ref).max():.3g}, max |dV| {np.abs(dv_ref).max():.3g}",
           flush=True)
-    assert max(errs) <= 2e-2, errs
+    assert max(errs) <= TOL["g"], errs
     # With 262144 keys per row a single P is about 1e-5 and these gradients are far below the absolute
     # bound, so it alone would pass an all-zero answer: also bound the error relative to the largest
     # reference value (bf16 rounding of P and dS: 2^-9 per term).
@@ -183,7 +187,7 @@ def test_ulysses_packed_fwd_bwd_sampled_rows():
     errs = dict(o=max_abs(to_host64(o_acc[idx]), ref[0]), lse=max_abs(to_host64(lse[:, idx]), ref[1]),
                 dq=max_abs(to_host64(dq[idx]), ref[2]))
     print("ulysses sampled-row errors", errs, flush=True)
-    assert errs["o"] <= 2e-2 and errs["lse"] <= 1e-3 and errs["dq"] <= 2e-2, errs
+    assert errs["o"] <= TOL["o"] and errs["lse"] <= TOL["lse"] and errs["dq"] <= TOL["g"], errs
     # dK / dV of one whole document, element by element: the shortest one that is complete (the
     # last one may be truncated); its rows see only its own keys, so the oracle problem is the
     # document by itself
@@ -195,7 +199,7 @@ def test_ulysses_packed_fwd_bwd_sampled_rows():
     doc_errs = dict(dk=max_abs(to_host64(dk[a:b]), ref_doc[3]), dv=max_abs(to_host64(dv[a:b]), ref_doc[4]),
                     dq=max_abs(to_host64(dq[a:b]), ref_doc[2]), o=max_abs(to_host64(o_acc[a:b]), ref_doc[0]))
     print(f"ulysses document {i} (rows {a}..{b}, {b - a} tokens): errors {doc_errs}", flush=True)
-    assert max(doc_errs.values()) <= 2e-2, doc_errs
+    assert max(doc_errs.values()) <= TOL["g"], doc_errs
     # per document: sum_j dV[j] = sum over heads and rows of the document of dO
     dvh = to_host64(dv)
     for a, b in zip(cu[:-1], cu[1:]):

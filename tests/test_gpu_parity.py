@@ -11,12 +11,12 @@ import torch
 from oracle import mmsp_oracle as orc
 from paper_2408_10188_amd import binding as B
 from paper_2408_10188_amd import ring, synth
-from tests.helpers import DEV, RankProblem, max_abs, nans, nans_like, to_dev, to_host64
+from tests.helpers import DEV, NORTH_STAR_TOL, RankProblem, max_abs, nans, nans_like, to_dev, to_host64
 
 pytestmark = pytest.mark.gpu
 
-TOL_BF16 = dict(o=2e-2, lse=1e-3, g=2e-2)
-TOL_F32 = dict(o=1e-5, lse=1e-5, g=1e-5)
+TOL_BF16 = NORTH_STAR_TOL["bf16"]
+TOL_F32 = NORTH_STAR_TOL["f32"]
 
 
 def _check_rank(prob, rank, tol, fused_merge=True, backward=True, two_streams=False):
@@ -46,6 +46,7 @@ def _check_rank(prob, rank, tol, fused_merge=True, backward=True, two_streams=Fa
 def test_tiny_fp32_rank0_fwd_merge_bwd():
     """Configuration 1: fp32, 2/1 heads, d 64, T 512, N 2, rank 0 -- both merge variants."""
     prob = RankProblem(synth.CONFIGS["tiny"])
+    assert TOL_F32 == dict(o=1e-5, lse=1e-5, g=1e-5)           # the named configuration gets the unscaled bounds
     a = _check_rank(prob, 0, TOL_F32, fused_merge=True)
     b = _check_rank(prob, 0, TOL_F32, fused_merge=False)
     assert max_abs(to_host64(a["o_acc"]), to_host64(b["o_acc"])) <= 2e-6
@@ -208,6 +209,65 @@ def test_dkdv_with_and_without_cut_query_ranges(n_k, n_q, documents):
     if not documents:                           # every pair visible: the variant without masking
         _run_step(True, 8, 8, 128, n_q, n_k, dict(q_row0=0, n_q=n_q, k_row0=0, n_k=n_k, mask=B.MMSP_MASK_FULL),
                   seed=61 + n_q)
+
+
+def test_c_caller_runs_a_step(tmp_path):
+    """A C99 translation unit that includes only the public header runs one forward and one
+    backward step on this process's device buffers; its results equal the binding's bit for bit
+    and match the oracle."""
+    import ctypes
+    import os
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.dirname(B.LIB_PATH)
+    so = tmp_path / "libc_abi_step.so"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-shared", "-fPIC", "-I", os.path.join(root, "include"),
+                    os.path.join(root, "tests", "c_abi_step.c"), "-o", str(so), "-L", libdir, "-lmmsp",
+                    "-Wl,-rpath," + libdir], check=True)
+    c = ctypes.CDLL(str(so))
+    P, I, F = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    c.c_client_step_fwd.argtypes = [P] * 5 + [I] * 5 + [F]
+    c.c_client_step_bwd.argtypes = [P] * 10 + [I] * 5 + [F]
+    c.c_client_last_error.restype = ctypes.c_char_p
+    n_q, n_k, Hq, Hkv, d = 150, 333, 4, 2, 128
+    scale = 1 / math.sqrt(d)
+    rng = np.random.default_rng(77)
+    rnd = lambda *s: synth.bf16_round(rng.standard_normal(s, dtype=np.float32) * 0.5)
+    q, k, v, do = rnd(n_q, Hq, d), rnd(n_k, Hkv, d), rnd(n_k, Hkv, d), rnd(n_q, Hq, d)
+    qd, kd, vd, dod = (to_dev(x, True) for x in (q, k, v, do))
+    ptr = lambda t: t.data_ptr()
+    res = []
+    for through_c in (True, False):
+        o, lse, delta = nans(n_q, Hq, d), nans(Hq, n_q), nans(Hq, n_q)
+        dq = torch.zeros(n_q, Hq, d, dtype=torch.float32, device=DEV)
+        dk, dv = nans(n_k, Hkv, d), nans(n_k, Hkv, d)
+        shape = ring.shape_for(qd, kd, B.MMSP_BF16, n_q, scale)
+        blk = B.make_block(0, n_q, 0, n_k, B.MMSP_MASK_CAUSAL_DIAG, n_k - n_q, 0)
+        if through_c:
+            st = c.c_client_step_fwd(ptr(qd), ptr(kd), ptr(vd), ptr(o), ptr(lse), n_q, n_k, Hq, Hkv, d, scale)
+            assert st == 0, c.c_client_last_error()
+        else:
+            B.mmsp_attn_step_fwd(shape, blk, qd, kd, vd, o, lse, 0)
+        o_final = o.to(torch.bfloat16)
+        if through_c:
+            st = c.c_client_step_bwd(ptr(qd), ptr(kd), ptr(vd), ptr(o_final), ptr(dod), ptr(lse), ptr(delta), ptr(dq), ptr(dk),
+                                     ptr(dv), n_q, n_k, Hq, Hkv, d, scale)
+            assert st == 0, c.c_client_last_error()
+        else:
+            B.mmsp_attn_step_bwd_static(shape, blk, qd, kd, vd, o_final, dod, lse, delta, 1, dq, dk, dv, 0)
+        torch.cuda.synchronize()
+        res.append([t.cpu().numpy() for t in (o, lse, delta, dq, dk, dv)])
+    for a, b in zip(*res):
+        assert np.array_equal(a, b)
+    ob = dict(q_row0=0, n_q=n_q, k_row0=0, n_k=n_k, q_pos0=n_k - n_q, k_pos0=0, mask=B.MMSP_MASK_CAUSAL_DIAG)
+    q64, k64, v64, do64 = (x.astype(np.float64) for x in (q, k, v, do))
+    O_ref, L_ref = orc.step_fwd(q64, k64, v64, ob, scale, None)
+    assert max_abs(res[0][0], O_ref) <= TOL_BF16["o"] and max_abs(res[0][1], L_ref) <= TOL_BF16["lse"]
+    dq_ref, dk_ref, dv_ref = orc.step_bwd(q64, k64, v64, do64, L_ref, orc.delta(do64, O_ref), ob, scale, None)
+    assert max(max_abs(res[0][3], dq_ref), max_abs(res[0][4], dk_ref), max_abs(res[0][5], dv_ref)) <= TOL_BF16["g"]
 
 
 def test_merge_and_cast_kernel():

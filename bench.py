@@ -114,7 +114,7 @@ def bench_ulysses(args, cfg, torch, np, B, ring, synth, acc):
     def bwd():
         dq.zero_()
         ring.ulysses_backward(shape, T, q, k, v, cud, n_docs, o_final, d_o, lse, delta, dq, dk, dv, ws=ws, ws_bytes=ws_bytes,
-                              side=side)
+                              side=side, cu_host=cu, q_block=args.query_block or None)
 
     def one_pass():
         fwd(); bwd()
@@ -245,6 +245,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="forward-only zigzag workloads: capture one pass in a HIP graph and time its replays (the launches "
                          "of a short pass then cost one submission); every replay is checked against the eager result")
+    ap.add_argument("--query-block", type=int, default=0,
+                    help="ulysses: cut the backward into launches over query blocks of this many rows (default 0: one launch "
+                         "per kernel over the whole sequence, whose workgroups drift apart and re-read Q / dO from HBM)")
     ap.add_argument("--cpu-rows", type=int, default=32, help="query rows per chunk in the oracle sample")
     ap.add_argument("--data-movement", action="store_true",
                     help="only time the HBM-bound sharding kernels at the 256K-token shapes (zigzag gather / scatter of Q, "

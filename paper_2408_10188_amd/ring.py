@@ -157,19 +157,74 @@ def ulysses_forward(shape, T, q, k, v, cu_seqlens, n_docs, o_acc, lse, o_final=N
         B.mmsp_attn_merge(shape, 0, T, o_acc, lse, None, None, o_final, stream=stream)
 
 
+def ulysses_blocks(T, cu_host, q_block):
+    """Cuts the head-shard step into query blocks of q_block rows.  Yields (q_row0, n_q, k_row0,
+    n_k, masked): the block's rows against the keys from the start of its first row's document
+    up to the block's own start (every pair visible when the block lies inside one document:
+    masked = False), then against its own rows (document-causal, masked = True).  Rows outside
+    every document see nothing and are left to the masked call."""
+    import bisect
+    cu = [int(x) for x in cu_host]
+    for r0 in range(0, T, q_block):
+        r1 = min(T, r0 + q_block)
+        i = bisect.bisect_right(cu, r0) - 1
+        one_document = 0 <= i < len(cu) - 1 and r1 <= cu[i + 1]
+        if one_document:
+            if r0 > cu[i]:
+                yield r0, r1 - r0, cu[i], r0 - cu[i], False
+            yield r0, r1 - r0, r0, r1 - r0, True
+        else:
+            k0 = min(r0, max(0, cu[max(i, 0)])) if i >= 0 else r0
+            yield r0, r1 - r0, k0, r1 - k0, True
+
+
 def ulysses_backward(shape, T, q, k, v, cu_seqlens, n_docs, o_final, d_o, lse, delta, dq, dk, dv, stream=0, ws=None,
-                     ws_bytes=0, side=None):
-    """With `side` the dQ kernel runs on the current torch stream and the dK/dV kernel on side.stream."""
-    blk = B.make_block(0, T, 0, T, B.MMSP_MASK_CAUSAL_DIAG, 0, 0, cu_seqlens, n_docs)
+                     ws_bytes=0, side=None, cu_host=None, q_block=None):
+    """dq must be zero on entry.  By default one launch per kernel covers the whole sequence.
+    With cu_host (host copy of cu_seqlens) and q_block the step is cut into query blocks of
+    q_block rows, launched one after the other: the workgroups of a launch then walk the same
+    Q / dO rows (dK/dV kernel) at the same time and share them in L2, where one launch over a
+    long document lets them drift apart and re-read the operands (measured: an order of
+    magnitude less HBM traffic, but no shorter, because every block's launch ends in a partly
+    filled round of workgroups).  dk / dv rows are overwritten by the first block that reaches
+    them and added to by later ones.
+    With `side` the dK/dV kernels run on the current torch stream and the dQ kernels on side.stream."""
+    import torch
+    main = torch.cuda.current_stream() if side is not None else None
+    s_main = main.cuda_stream if side is not None else stream
+    B.mmsp_attn_delta(shape, 0, T, o_final, d_o, delta, stream=s_main)
     if side is not None:
-        import torch
-        main = torch.cuda.current_stream()
-        B.mmsp_attn_delta(shape, 0, T, o_final, d_o, delta, stream=main.cuda_stream)
-        side.stream.wait_stream(main)
-        B.mmsp_attn_step_bwd(shape, blk, q, k, v, None, d_o, lse, delta, False, dq, None, None, False, ws, ws_bytes,
-                             main.cuda_stream)
-        B.mmsp_attn_step_bwd(shape, blk, q, k, v, None, d_o, lse, delta, False, None, dk, dv, False, side.ws,
-                             side.ws_bytes, side.handle)
+        side.stream.wait_stream(main)           # delta and the caller's zeroing of dq
+    if cu_host is None or not q_block:
+        blocks = [(0, T, 0, T, True)]
+    else:
+        blocks = list(ulysses_blocks(T, cu_host, q_block))
+    written = 0                                 # dk / dv rows below this index hold a result already
+    for r0, n_q, k0, n_k, masked in blocks:
+        if masked:
+            blk = B.make_block(r0, n_q, k0, n_k, B.MMSP_MASK_CAUSAL_DIAG, r0, k0, cu_seqlens, n_docs)
+        else:
+            blk = B.make_block(r0, n_q, k0, n_k, B.MMSP_MASK_FULL, r0, k0)
+        # keys [k0, k0 + n_k): the part below `written` accumulates, the rest is new
+        parts = []
+        if k0 < written:
+            parts.append((k0, min(written, k0 + n_k) - k0, True))
+        if k0 + n_k > written:
+            parts.append((max(k0, written), k0 + n_k - max(k0, written), False))
+        if len(parts) == 1:
+            B.mmsp_attn_step_bwd(shape, blk, q, k, v, None, d_o, lse, delta, False, None, dk, dv, parts[0][2],
+                                 ws, ws_bytes, s_main)
+        else:
+            for kk, nn, accumulate in parts:
+                sub = B.make_block(r0, n_q, kk, nn, blk.mask, r0, kk, cu_seqlens if masked else None, n_docs if masked else 0)
+                B.mmsp_attn_step_bwd(shape, sub, q, k, v, None, d_o, lse, delta, False, None, dk, dv, accumulate,
+                                     ws, ws_bytes, s_main)
+        written = max(written, k0 + n_k)
+        if side is not None:
+            B.mmsp_attn_step_bwd(shape, blk, q, k, v, None, d_o, lse, delta, False, dq, None, None, False,
+                                 side.ws, side.ws_bytes, side.handle)
+        else:
+            B.mmsp_attn_step_bwd(shape, blk, q, k, v, None, d_o, lse, delta, False, dq, None, None, False,
+                                 ws, ws_bytes, s_main)
+    if side is not None:
         main.wait_stream(side.stream)
-        return
-    B.mmsp_attn_step_bwd(shape, blk, q, k, v, o_final, d_o, lse, delta, True, dq, dk, dv, False, ws, ws_bytes, stream)

@@ -170,8 +170,8 @@ def test_ulysses_packed_fwd_bwd_sampled_rows():
     o_final = nans_like(qd)
     delta = nans_like(lse)
     dq = torch.zeros_like(o_acc)
-    dk = torch.zeros(T, Hkv, d, dtype=torch.float32, device=DEV)
-    dv = torch.zeros_like(dk)
+    dk = nans(T, Hkv, d)
+    dv = nans(T, Hkv, d)
     ws_bytes = ring.workspace_bytes(shape, T, T)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
     ring.ulysses_forward(shape, T, qd, kd, vd, cud, len(cu) - 1, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes)

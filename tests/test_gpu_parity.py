@@ -211,6 +211,37 @@ def test_dkdv_with_and_without_cut_query_ranges(n_k, n_q, documents):
                   seed=61 + n_q)
 
 
+@pytest.mark.parametrize("two_streams", [False, True])
+@pytest.mark.parametrize("cu", [[0, 100, 101, 333, 400, 700], [50, 300, 650], [0, 700]])
+def test_head_shard_backward_in_query_blocks(cu, two_streams):
+    """ring.ulysses_backward cut into 128-row query blocks (document boundaries inside blocks,
+    blocks inside one document, rows outside every document): every dQ, dK and dV element
+    against the oracle, and dK/dV written without relying on their previous contents."""
+    T, Hq, Hkv, d = 700, 4, 2, 128
+    scale = 1 / math.sqrt(d)
+    rng = np.random.default_rng(90 + len(cu))
+    rnd = lambda *s: synth.bf16_round(rng.standard_normal(s, dtype=np.float32) * 0.5)
+    q, k, v, do = rnd(T, Hq, d), rnd(T, Hkv, d), rnd(T, Hkv, d), rnd(T, Hq, d)
+    qd, kd, vd, dod = (to_dev(x, True) for x in (q, k, v, do))
+    cua = np.asarray(cu, dtype=np.int32)
+    cud = torch.from_numpy(cua).to(DEV)
+    shape = ring.shape_for(qd, kd, B.MMSP_BF16, T, scale)
+    o_acc, lse, o_final, delta = nans(T, Hq, d), nans(Hq, T), nans_like(qd), nans(Hq, T)
+    dq = torch.zeros(T, Hq, d, dtype=torch.float32, device=DEV)
+    dk, dv = nans(T, Hkv, d), nans(T, Hkv, d)
+    ws_bytes = ring.workspace_bytes(shape, T, T)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    side = ring.SideLane(torch.cuda.Stream(), None, None, torch.empty_like(ws), ws_bytes) if two_streams else None
+    ring.ulysses_forward(shape, T, qd, kd, vd, cud, len(cu) - 1, o_acc, lse, o_final, ws=ws, ws_bytes=ws_bytes)
+    ring.ulysses_backward(shape, T, qd, kd, vd, cud, len(cu) - 1, o_final, dod, lse, delta, dq, dk, dv, ws=ws,
+                          ws_bytes=ws_bytes, side=side, cu_host=cua, q_block=128)
+    torch.cuda.synchronize()
+    ref = orc.causal_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), scale, cu_seqlens=cua,
+                               dO=do.astype(np.float64))
+    errs = [max_abs(to_host64(x), r) for x, r in zip((o_acc, lse, dq, dk, dv), ref)]
+    assert errs[0] <= TOL_BF16["o"] and errs[1] <= TOL_BF16["lse"] and max(errs[2:]) <= TOL_BF16["g"], errs
+
+
 def test_c_caller_runs_a_step(tmp_path):
     """A C99 translation unit that includes only the public header runs one forward and one
     backward step on this process's device buffers; its results equal the binding's bit for bit

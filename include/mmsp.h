@@ -175,13 +175,14 @@ mmsp_status mmsp_zigzag_scatter(int64_t T, int32_t N, int64_t row_bytes, const v
 mmsp_status mmsp_a2a_pack_heads(int64_t n_tokens, int32_t U, int64_t slice_bytes, const void* x, void* y, void* hip_stream);
 mmsp_status mmsp_a2a_unpack_heads(int64_t n_tokens, int32_t U, int64_t slice_bytes, const void* y, void* x, void* hip_stream);
 
-/* Bytes of device workspace the step calls need for blocks of at most n_q_max x n_k_max rows
- * (0 for f32).  The bf16 kernels use it for token-contiguous (transposed) copies of tiles that
- * each call rebuilds before its main kernel and, in the backward, for partial dK/dV sums of
- * key tiles whose query range was cut into several workgroups (a fixed 64 MiB); nothing in it
- * outlives a call.  `backward` != 0 asks for mmsp_attn_step_bwd.  The workspace must be 16-byte aligned; a call given less
- * returns MMSP_ERR_WORKSPACE_TOO_SMALL.  Two calls that may overlap in time (different
- * streams) need separate workspaces. */
+/* Bytes of device workspace the step calls need for blocks of at most n_q_max x n_k_max rows.
+ * The forward needs none (0; its kernels read the caller's tensors in place), neither does
+ * f32.  The bf16 backward (`backward` != 0) uses the workspace for the block's row statistics
+ * (-LSE and delta, padded to whole tiles: 8 bytes per query row and head) and for partial
+ * dK/dV sums of key tiles whose query range was cut into several workgroups (a fixed 64 MiB);
+ * nothing in it outlives the kernels of a call.  The workspace must be 16-byte aligned; a call
+ * given less returns MMSP_ERR_WORKSPACE_TOO_SMALL.  Two calls that may overlap in time
+ * (different streams) need separate workspaces. */
 size_t mmsp_workspace_bytes(const mmsp_shape* shape, int64_t n_q_max, int64_t n_k_max, int backward);
 
 /* One ring step, forward (the per-rank attention of one ring round; comparison figure,

@@ -15,7 +15,8 @@
 // independent and interleaved in program order.  The loop is therefore software-pipelined inside
 // every wavefront: while the matrix pipe works on P.V of tile t-1 the vector units take the
 // maximum and the first half of the exponentials of tile t, and while it works on S of tile t+1
-// they take the second half.  Scheduling-group barriers pin that interleaving.
+// they take the second half.  The interleaving is written out step by step (one matrix
+// instruction per step) and pinned with empty asm statements and scheduling barriers.
 // Tiles wholly outside every row's visible key interval are skipped; only tiles that cut an
 // interval boundary (the causal diagonal, a document start) pay for masking.
 #include "mfma_tiles.h"

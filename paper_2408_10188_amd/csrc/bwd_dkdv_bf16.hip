@@ -60,6 +60,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs 
   __shared__ __attribute__((aligned(1024))) float st3[128];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the same value in a scalar register (LDS targets of the copies)
   const int half = lane >> 5, col = lane & 31;
 
   int kvh, item;                    // item = key tile * nsplit + range
@@ -167,9 +168,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs 
     };
     auto fetch_piece = [&](const Fetch& f, int piece, char* qdst, char* odst, float* sdst) {
       constexpr int W = 16 / kCopies;
-      if (piece < kCopies) dma16(f.q + f.qo.o[piece], qdst + (wave + piece * W) * 1024);
-      else if (piece < 2 * kCopies) dma16(f.d_o + f.dd.o[piece - kCopies], odst + (wave + (piece - kCopies) * W) * 1024);
-      else dma4(f.st, reinterpret_cast<char*>(sdst + (wave & 1) * 64));   // even wavefronts fetch -LSE*log2e, odd ones delta
+      if (piece < kCopies) dma16(f.q + f.qo.o[piece], qdst, (wave_s + piece * W) * 1024);
+      else if (piece < 2 * kCopies) dma16(f.d_o + f.dd.o[piece - kCopies], odst, (wave_s + (piece - kCopies) * W) * 1024);
+      else dma4(f.st, sdst, (wave_s & 1) * 256);        // even wavefronts fetch -LSE*log2e, odd ones delta
     };
     auto fetch = [&](char* qdst, char* odst, float* sdst) {
       const Fetch f = fetch_begin();

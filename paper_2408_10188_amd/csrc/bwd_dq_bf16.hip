@@ -32,6 +32,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
   __shared__ __attribute__((aligned(1024))) char vs2[kTileBytes];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the same value in a scalar register (LDS targets of the copies)
   const int half = lane >> 5, col = lane & 31;
 
   // workgroup -> (head, query tile): the workgroups of a KV head share an XCD, later (heavier
@@ -90,9 +91,9 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
   auto fetch = [&](char* kdst, char* vdst) {            // past the end the last tile is fetched again
     constexpr int W = 16 / kCopies;
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) dma16(pk[i], kdst + (wave + i * W) * 1024);
+    for (int i = 0; i < kCopies; ++i) dma16(pk[i], kdst, (wave_s + i * W) * 1024);
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) dma16(pv[i], vdst + (wave + i * W) * 1024);
+    for (int i = 0; i < kCopies; ++i) dma16(pv[i], vdst, (wave_s + i * W) * 1024);
     if (f_kt < kt1) {
       ++f_kt;
       if (a.n_k - f_kt * kBN >= kBN) {

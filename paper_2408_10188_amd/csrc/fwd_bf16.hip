@@ -43,6 +43,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
   __shared__ __attribute__((aligned(1024))) char vslot2[kTileBytes];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the same value in a scalar register (LDS targets of the copies)
   const int half = lane >> 5, col = lane & 31;
 
   // Workgroup -> (head, query tile).  Workgroups are dealt round-robin to the 8 XCDs; the
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
   auto fetch = [&](Cursor& cu, const char* base, char* dst) {   // the cursor's tile -> slot dst; past the end the last tile again
     constexpr int W = 16 / kCopies;
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) dma16(cu.p[i], dst + (wave + i * W) * 1024);
+    for (int i = 0; i < kCopies; ++i) dma16(cu.p[i], dst, (wave_s + i * W) * 1024);
     if (cu.kt < kt1) {
       if (a.n_k - (cu.kt + 1) * kBN >= kBN) {
         ++cu.kt;

@@ -57,14 +57,17 @@ constexpr int kTileBytes = 64 * 128 * 2;     // 16 KiB: one 64 x 128 bf16 tile
 // (the counter retires in order), never too weak.  M0 (the copy's LDS base) is a register the
 // compiler reserves and sets itself right before each of its own uses; nothing else in these
 // kernels uses it.
-__device__ __forceinline__ void dma16(const char* gptr, char* lds_wave_base) {
-  const uint32_t lds = __builtin_amdgcn_readfirstlane(
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_wave_base);
+// `lds_array` is a __shared__ array (its LDS address is a constant the compiler folds), `byte_offset`
+// a wavefront-uniform offset inside it that the caller keeps in a scalar register.
+__device__ __forceinline__ uint32_t lds_address(const void* lds_array) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)lds_array;
+}
+__device__ __forceinline__ void dma16(const char* gptr, const void* lds_array, int byte_offset) {
+  const uint32_t lds = lds_address(lds_array) + (uint32_t)byte_offset;
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(gptr) : "memory");
 }
-__device__ __forceinline__ void dma4(const char* gptr, char* lds_wave_base) {   // 4 bytes per lane
-  const uint32_t lds = __builtin_amdgcn_readfirstlane(
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_wave_base);
+__device__ __forceinline__ void dma4(const char* gptr, const void* lds_array, int byte_offset) {   // 4 bytes per lane
+  const uint32_t lds = lds_address(lds_array) + (uint32_t)byte_offset;
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds), "v"(gptr) : "memory");
 }
 
@@ -93,14 +96,6 @@ __device__ __forceinline__ void lds_barrier_after_write() {
 // Offsets are bytes from the tile's first row and fit 32 bits.
 template <int kCopies>
 struct DmaOffs { uint32_t o[kCopies]; };
-
-template <int kCopies>
-__device__ __forceinline__ void dma_tile_n(const char* tile_ptr /* uniform */, const DmaOffs<kCopies>& off, char* lds_tile,
-                                           int wave) {
-  constexpr int W = 16 / kCopies;
-#pragma unroll
-  for (int i = 0; i < kCopies; ++i) dma16(tile_ptr + off.o[i], lds_tile + (wave + i * W) * 1024);
-}
 
 // ---------------------------------------------------------------------------------------
 // TileS: a [64 rows][128 cols] bf16 tile in its natural orientation (row = token, col = d),

@@ -140,7 +140,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs 
     const int64_t q_tile_bytes = (int64_t)kBQ * a.q_ts * 2, do_tile_bytes = (int64_t)kBQ * a.Hq * 256;
     const int64_t q_head_bytes = (int64_t)a.q_hs * 2;
     const int64_t st_head_bytes = (int64_t)w.n_qtiles * kBQ * 4;
-    const char* stat_src = reinterpret_cast<const char*>((wave & 1) ? w.dl : w.nl2) + (int64_t)kvh * a.group * st_head_bytes + lane * 4;
+    const char* stat_src = reinterpret_cast<const char*>((wave_s & 1) ? w.dl : w.nl2) + (int64_t)kvh * a.group * st_head_bytes;
     const DmaOffs<kCopies> qoff_full = dma_s_offsets<kCopies>(a.q_ts, kBQ, wave, lane);
     const DmaOffs<kCopies> dooff_full = dma_s_offsets<kCopies>((int64_t)a.Hq * 128, kBQ, wave, lane);
     int f_hg = split % a.group, f_qt = qt1 - split / a.group, f_it = 0;   // element the next fetch takes
@@ -168,9 +168,9 @@ __global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs 
     };
     auto fetch_piece = [&](const Fetch& f, int piece, char* qdst, char* odst, float* sdst) {
       constexpr int W = 16 / kCopies;
-      if (piece < kCopies) dma16(f.q + f.qo.o[piece], qdst, (wave_s + piece * W) * 1024);
-      else if (piece < 2 * kCopies) dma16(f.d_o + f.dd.o[piece - kCopies], odst, (wave_s + (piece - kCopies) * W) * 1024);
-      else dma4(f.st, sdst, (wave_s & 1) * 256);        // even wavefronts fetch -LSE*log2e, odd ones delta
+      if (piece < kCopies) dma16(f.q, f.qo.o[piece], qdst, (wave_s + piece * W) * 1024);
+      else if (piece < 2 * kCopies) dma16(f.d_o, f.dd.o[piece - kCopies], odst, (wave_s + (piece - kCopies) * W) * 1024);
+      else dma4(f.st, (uint32_t)lane * 4, sdst, (wave_s & 1) * 256);   // even wavefronts fetch -LSE*log2e, odd ones delta
     };
     auto fetch = [&](char* qdst, char* odst, float* sdst) {
       const Fetch f = fetch_begin();

@@ -73,39 +73,26 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
   const char* kbase = reinterpret_cast<const char*>(a.k) + kv_off;
   const char* vbase = reinterpret_cast<const char*>(a.v) + kv_off;
   const int64_t tile_bytes = (int64_t)kBN * a.kv_ts * 2;
-  // Per-lane source addresses of the next tile to fetch, carried from tile to tile and advanced
-  // by additions.  (They stay in the same registers for the whole loop: a copy's address
-  // register that is recycled for an LDS read right behind it makes the compiler wait for every
-  // copy in flight.)
-  const char* pk[kCopies];
-  const char* pv[kCopies];
+  // Source of a copy = the tile's address (wavefront-uniform, advanced by scalar additions) + a
+  // per-lane offset that is the same for every whole tile.
+  const DmaOffs<kCopies> off_full = dma_s_offsets<kCopies>(a.kv_ts, kBN, wave, lane);
   int f_kt = kt0;                                       // tile the next fetch takes
-  auto point_at = [&](int kt) {
-    const DmaOffs<kCopies> off = dma_s_offsets<kCopies>(a.kv_ts, min(kBN, a.n_k - kt * kBN), wave, lane);   // ragged last tile: rows past the end repeat the last row
-#pragma unroll
-    for (int i = 0; i < kCopies; ++i) {
-      pk[i] = kbase + (int64_t)kt * tile_bytes + off.o[i];
-      pv[i] = vbase + (int64_t)kt * tile_bytes + off.o[i];
-    }
-  };
+  int64_t f_tile = (int64_t)kt0 * tile_bytes;           // its byte offset from kbase / vbase
   auto fetch = [&](char* kdst, char* vdst) {            // past the end the last tile is fetched again
     constexpr int W = 16 / kCopies;
+    DmaOffs<kCopies> off = off_full;
+    const int left = a.n_k - f_kt * kBN;
+    if (left < kBN) off = dma_s_offsets<kCopies>(a.kv_ts, left, wave, lane);   // ragged last tile: rows past the end repeat the last row
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) dma16(pk[i], kdst, (wave_s + i * W) * 1024);
+    for (int i = 0; i < kCopies; ++i) dma16(kbase + f_tile, off.o[i], kdst, (wave_s + i * W) * 1024);
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) dma16(pv[i], vdst, (wave_s + i * W) * 1024);
+    for (int i = 0; i < kCopies; ++i) dma16(vbase + f_tile, off.o[i], vdst, (wave_s + i * W) * 1024);
     if (f_kt < kt1) {
       ++f_kt;
-      if (a.n_k - f_kt * kBN >= kBN) {
-#pragma unroll
-        for (int i = 0; i < kCopies; ++i) { pk[i] += tile_bytes; pv[i] += tile_bytes; }
-      } else {
-        point_at(f_kt);
-      }
+      f_tile += tile_bytes;
     }
   };
   if (kt0 <= kt1) {
-    point_at(kt0);
     fetch(ks0, vs0);
     fetch(ks1, vs1);
   }

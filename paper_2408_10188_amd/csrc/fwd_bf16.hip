@@ -89,39 +89,28 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
   const char* kbase = reinterpret_cast<const char*>(a.k) + ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
   const char* vbase = reinterpret_cast<const char*>(a.v) + ((int64_t)a.k_row0 * a.kv_ts + (int64_t)kvh * a.kv_hs) * 2;
   const int64_t tile_bytes = (int64_t)kBN * a.kv_ts * 2;
-  // Per-lane source addresses of the next K tile and the next V tile to fetch, carried from tile
-  // to tile and advanced by additions.  (They stay in the same registers for the whole loop: a
-  // copy's address register that is recycled for an LDS read right behind it makes the compiler
-  // wait for every copy in flight.)
-  struct Cursor { const char* p[kCopies]; int kt; };
-  auto point_at = [&](Cursor& cu, const char* base, int kt) {
-    const DmaOffs<kCopies> off = dma_s_offsets<kCopies>(a.kv_ts, min(kBN, a.n_k - kt * kBN), wave, lane);   // ragged last tile: rows past the end repeat the last row
-    cu.kt = kt;
-#pragma unroll
-    for (int i = 0; i < kCopies; ++i) cu.p[i] = base + (int64_t)kt * tile_bytes + off.o[i];
-  };
+  // Source of a copy = the tile's address (wavefront-uniform, advanced by scalar additions) + a
+  // per-lane offset that is the same for every whole tile.  K and V have a cursor each.
+  const DmaOffs<kCopies> off_full = dma_s_offsets<kCopies>(a.kv_ts, kBN, wave, lane);
+  struct Cursor { int64_t tile; int kt; };              // byte offset of the tile from kbase / vbase, tile index
   auto fetch = [&](Cursor& cu, const char* base, char* dst) {   // the cursor's tile -> slot dst; past the end the last tile again
     constexpr int W = 16 / kCopies;
+    DmaOffs<kCopies> off = off_full;
+    const int left = a.n_k - cu.kt * kBN;
+    if (left < kBN) off = dma_s_offsets<kCopies>(a.kv_ts, left, wave, lane);   // ragged last tile: rows past the end repeat the last row
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) dma16(cu.p[i], dst, (wave_s + i * W) * 1024);
+    for (int i = 0; i < kCopies; ++i) dma16(base + cu.tile, off.o[i], dst, (wave_s + i * W) * 1024);
     if (cu.kt < kt1) {
-      if (a.n_k - (cu.kt + 1) * kBN >= kBN) {
-        ++cu.kt;
-#pragma unroll
-        for (int i = 0; i < kCopies; ++i) cu.p[i] += tile_bytes;
-      } else {
-        point_at(cu, base, cu.kt + 1);
-      }
+      ++cu.kt;
+      cu.tile += tile_bytes;
     }
   };
   // Copies are issued in groups of 2 kCopies per wavefront so that "all but the newest group"
   // is one s_waitcnt value: {K(kt0), V(kt0)}, {K(kt0+1), K(kt0+2)}, then {K(t+3), V(t+1)} at the
   // top of iteration t.
   const bool any_tile = kt0 <= kt1;
-  Cursor kc, vc;
+  Cursor kc{(int64_t)kt0 * tile_bytes, kt0}, vc{(int64_t)kt0 * tile_bytes, kt0};
   if (any_tile) {
-    point_at(kc, kbase, kt0);
-    point_at(vc, vbase, kt0);
     fetch(kc, kbase, kslot0);
     fetch(vc, vbase, vslot0);
     fetch(kc, kbase, kslot1);

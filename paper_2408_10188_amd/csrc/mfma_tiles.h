@@ -62,13 +62,14 @@ constexpr int kTileBytes = 64 * 128 * 2;     // 16 KiB: one 64 x 128 bf16 tile
 __device__ __forceinline__ uint32_t lds_address(const void* lds_array) {
   return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)lds_array;
 }
-__device__ __forceinline__ void dma16(const char* gptr, const void* lds_array, int byte_offset) {
+// Source address = wavefront-uniform `base` (scalar register pair) + this lane's 32-bit byte `offset`.
+__device__ __forceinline__ void dma16(const char* base, uint32_t offset, const void* lds_array, int byte_offset) {
   const uint32_t lds = lds_address(lds_array) + (uint32_t)byte_offset;
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(gptr) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds), "v"(offset), "s"(base) : "memory");
 }
-__device__ __forceinline__ void dma4(const char* gptr, const void* lds_array, int byte_offset) {   // 4 bytes per lane
+__device__ __forceinline__ void dma4(const char* base, uint32_t offset, const void* lds_array, int byte_offset) {   // 4 bytes per lane
   const uint32_t lds = lds_address(lds_array) + (uint32_t)byte_offset;
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds), "v"(gptr) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds), "v"(offset), "s"(base) : "memory");
 }
 
 // Bare workgroup barrier for the asynchronous-copy pipelines.  __syncthreads() (and any

@@ -44,20 +44,25 @@ constexpr int kDepth = 4;                        // LDS operand reads in flight 
 template <bool kMask>
 __global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs a, BwdWorkspace w, int n_kt, int xcd_per_kv,
                                                                        int nsplit) {
-  // One array per ring slot, selected at compile time, so that the compiler can tell the reads of
-  // one slot from the copies in flight into another.
-  __shared__ __attribute__((aligned(1024))) char qs0[kTileBytes];    // Q tiles, TileS
-  __shared__ __attribute__((aligned(1024))) char qs1[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char qs2[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char qs3[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char os0[kTileBytes];    // dO tiles, TileS
-  __shared__ __attribute__((aligned(1024))) char os1[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char os2[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char os3[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) float st0[128];          // [0,64) -LSE*log2e, [64,128) delta
-  __shared__ __attribute__((aligned(1024))) float st1[128];
-  __shared__ __attribute__((aligned(1024))) float st2[128];
-  __shared__ __attribute__((aligned(1024))) float st3[128];
+  // LDS map: four Q tile slots in [0, 64 KiB), four dO tile slots in [64 KiB, 128 KiB), then the four
+  // statistics slots.  Slots are selected at compile time (the loop is unrolled four tiles deep).
+  // An LDS instruction's immediate offset reaches 64 KiB: reads of the upper regions go through
+  // per-lane base registers that already hold the region's start (na_o, ta_o, so_st below), so
+  // that no read needs an address addition of its own.
+  constexpr int kQRegion = 0, kORegion = 4 * kTileBytes, kStRegion = 8 * kTileBytes;
+  __shared__ __attribute__((aligned(1024))) char lds[kStRegion + 4 * 512];
+  char* const qs0 = lds + kQRegion;                     // Q tiles, TileS
+  char* const qs1 = qs0 + kTileBytes;
+  char* const qs2 = qs1 + kTileBytes;
+  char* const qs3 = qs2 + kTileBytes;
+  char* const os0 = lds + kORegion;                     // dO tiles, TileS
+  char* const os1 = os0 + kTileBytes;
+  char* const os2 = os1 + kTileBytes;
+  char* const os3 = os2 + kTileBytes;
+  float* const st0 = reinterpret_cast<float*>(lds + kStRegion);   // [0,64) -LSE*log2e, [64,128) delta
+  float* const st1 = st0 + 128;
+  float* const st2 = st1 + 128;
+  float* const st3 = st2 + 128;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the same value in a scalar register (LDS targets of the copies)
@@ -193,6 +198,20 @@ __global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs 
       ta[db][1] = tile_s_tr_offset(lane, db, 1);
     }
     const int so = half * 4;                             // statistics of rows (i/4)*8 + half*4 + i%4: float4 at so + 8 g4
+    // the same per-lane offsets with the start of the dO / statistics region added, kept opaque so
+    // that the compiler uses them as bases instead of rebuilding them from na / ta
+    int na_o[8], ta_o[4][2], so_st = so * 4 + kStRegion;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) { na_o[ks] = na[ks] + kORegion; asm volatile("" : "+v"(na_o[ks])); }
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      ta_o[db][0] = ta[db][0] + kORegion; asm volatile("" : "+v"(ta_o[db][0]));
+      ta_o[db][1] = ta[db][1] + kORegion; asm volatile("" : "+v"(ta_o[db][1]));
+    }
+    asm volatile("" : "+v"(so_st));
+    auto stat4 = [&](const float* slot, int first_float) {   // float4 of this lane's rows, first_float = offset inside the slot
+      return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(slot) - kStRegion + so_st + first_float * 4);
+    };
 
     // (head of the group, query tile) of the tile being computed
     int c_hg = split % a.group, c_qt = qt1 - split / a.group;
@@ -213,14 +232,20 @@ __global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs 
       if (n >= 64) { n -= 64; cq = nq; co = no; }
       const int ph = n >> 4, i = n & 15;
       if ((ph & 1) == 0) {                               // natural: k-step i / 2, Q for S (even), dO for dP (odd)
-        const char* t = ph == 0 ? ((i & 1) ? co : cq) : ((i & 1) ? no : nq);
-        return *reinterpret_cast<const u32x4*>(t + na[i >> 1] + (ph == 0 ? 8192 : 0));
+        const int at = ph == 0 ? 8192 : 0;
+        if (i & 1) return *reinterpret_cast<const u32x4*>((ph == 0 ? co : no) - kORegion + na_o[i >> 1] + at);
+        return *reinterpret_cast<const u32x4*>((ph == 0 ? cq : nq) + na[i >> 1] + at);
       }
       // transposed: i = 8 t' + 2 db + (0: dO^T for dV, 1: Q^T for dK)
       const int tq = i >> 3, db = (i >> 1) & 3, g = (ph == 1 ? 0 : 2) + tq;
-      const char* t = (i & 1) ? cq : co;
-      const u32x2 v0 = lds_read_tr(t + ta[db][0] + g * 4096);
-      const u32x2 v1 = lds_read_tr(t + ta[db][1] + g * 4096);
+      u32x2 v0, v1;
+      if (i & 1) {
+        v0 = lds_read_tr(cq + ta[db][0] + g * 4096);
+        v1 = lds_read_tr(cq + ta[db][1] + g * 4096);
+      } else {
+        v0 = lds_read_tr(co - kORegion + ta_o[db][0] + g * 4096);
+        v1 = lds_read_tr(co - kORegion + ta_o[db][1] + g * 4096);
+      }
       return mk4(v0.x, v0.y, v1.x, v1.y);
     };
 
@@ -287,7 +312,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs 
           // ---- phase A: S, dP of the following block beside dS of block blk ----
           float4 dl[4];
 #pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) dl[g4] = *reinterpret_cast<const float4*>(cs + 64 + blk * 32 + so + g4 * 8);
+          for (int g4 = 0; g4 < 4; ++g4) dl[g4] = stat4(cs, 64 + blk * 32 + g4 * 8);
 #pragma unroll
           for (int i = 0; i < 16; ++i) { s_nx[i] = 0.f; dp_nx[i] = 0.f; }
           uint32_t sw[8];
@@ -319,7 +344,7 @@ __global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs 
           const float* fs = blk == 0 ? cs + 32 : ns;     // -LSE*log2e of the following block's rows
           float4 nl[4];
 #pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) nl[g4] = *reinterpret_cast<const float4*>(fs + so + g4 * 8);
+          for (int g4 = 0; g4 < 4; ++g4) nl[g4] = stat4(fs, g4 * 8);
           uint32_t pw[8];
           f32x16 p_nx;
 #pragma unroll

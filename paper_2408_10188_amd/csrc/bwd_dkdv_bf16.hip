@@ -148,34 +148,44 @@ __global__ __launch_bounds__(64 * kWaves, 1) void bwd_dkdv_bf16_kernel(StepArgs 
     const char* stat_src = reinterpret_cast<const char*>((wave_s & 1) ? w.dl : w.nl2) + (int64_t)kvh * a.group * st_head_bytes;
     const DmaOffs<kCopies> qoff_full = dma_s_offsets<kCopies>(a.q_ts, kBQ, wave, lane);
     const DmaOffs<kCopies> dooff_full = dma_s_offsets<kCopies>((int64_t)a.Hq * 128, kBQ, wave, lane);
-    int f_hg = split % a.group, f_qt = qt1 - split / a.group, f_it = 0;   // element the next fetch takes
+    // the last query tile of the block may be ragged: rows past the end repeat the last row
+    const int qt_ragged = a.n_q % kBQ != 0 ? a.n_q / kBQ : -1;
+    const DmaOffs<kCopies> qoff_ragged = dma_s_offsets<kCopies>(a.q_ts, qt_ragged >= 0 ? a.n_q % kBQ : kBQ, wave, lane);
+    const DmaOffs<kCopies> dooff_ragged = dma_s_offsets<kCopies>((int64_t)a.Hq * 128, qt_ragged >= 0 ? a.n_q % kBQ : kBQ, wave, lane);
+    // Element the next fetch takes, and where its Q / dO / statistics rows start.  The three
+    // addresses are wavefront-uniform and move by additions only.
+    int f_hg = split % a.group, f_qt = qt1 - split / a.group, f_it = 0;
+    const char* f_q = qbase + f_hg * q_head_bytes + f_qt * q_tile_bytes;
+    const char* f_do = dobase + f_hg * 256 + f_qt * do_tile_bytes;
+    const char* f_st = stat_src + f_hg * st_head_bytes + f_qt * (kBQ * 4);
+    const int64_t step_q = nsplit * q_head_bytes, wrap_q = a.group * q_head_bytes + q_tile_bytes;
+    const int64_t step_do = nsplit * 256, wrap_do = a.group * 256 + do_tile_bytes;
+    const int64_t step_st = nsplit * st_head_bytes, wrap_st = a.group * st_head_bytes + kBQ * 4;
     // A fetch is issued in 2 kCopies + 1 pieces (one copy instruction each) so that the loop can
     // spread them between its matrix instructions: a copy holds up the issuing wavefront while
     // the memory pipeline accepts it, and with one wavefront per SIMD nobody else fills that gap.
-    struct Fetch { const char* q; const char* d_o; const char* st; DmaOffs<kCopies> qo, dd; };
+    struct Fetch { const char* q; const char* d_o; const char* st; bool ragged; };
     auto fetch_begin = [&]() {
       Fetch f;
-      const int left = a.n_q - f_qt * kBQ;              // < kBQ: ragged last tile, rows past the end repeat the last row
-      f.q = qbase + f_hg * q_head_bytes + f_qt * q_tile_bytes;
-      f.d_o = dobase + f_hg * 256 + f_qt * do_tile_bytes;
-      f.st = stat_src + f_hg * st_head_bytes + f_qt * (kBQ * 4);
-      f.qo = qoff_full; f.dd = dooff_full;
-      if (left < kBQ) {
-        f.qo = dma_s_offsets<kCopies>(a.q_ts, left, wave, lane);
-        f.dd = dma_s_offsets<kCopies>((int64_t)a.Hq * 128, left, wave, lane);
-      }
+      f.q = f_q; f.d_o = f_do; f.st = f_st;
+      f.ragged = f_qt == qt_ragged;
       if (f_it + 1 < niter) {                           // past the end the last tile is fetched again (into a free slot)
         ++f_it;
-        f_hg += nsplit;
-        while (f_hg >= a.group) { f_hg -= a.group; --f_qt; }
+        f_hg += nsplit; f_q += step_q; f_do += step_do; f_st += step_st;
+        while (f_hg >= a.group) { f_hg -= a.group; --f_qt; f_q -= wrap_q; f_do -= wrap_do; f_st -= wrap_st; }
       }
       return f;
     };
     auto fetch_piece = [&](const Fetch& f, int piece, char* qdst, char* odst, float* sdst) {
       constexpr int W = 16 / kCopies;
-      if (piece < kCopies) dma16(f.q, f.qo.o[piece], qdst, (wave_s + piece * W) * 1024);
-      else if (piece < 2 * kCopies) dma16(f.d_o, f.dd.o[piece - kCopies], odst, (wave_s + (piece - kCopies) * W) * 1024);
-      else dma4(f.st, (uint32_t)lane * 4, sdst, (wave_s & 1) * 256);   // even wavefronts fetch -LSE*log2e, odd ones delta
+      if (piece < kCopies) {
+        dma16(f.q, f.ragged ? qoff_ragged.o[piece] : qoff_full.o[piece], qdst, (wave_s + piece * W) * 1024);
+      } else if (piece < 2 * kCopies) {
+        const int p = piece - kCopies;
+        dma16(f.d_o, f.ragged ? dooff_ragged.o[p] : dooff_full.o[p], odst, (wave_s + p * W) * 1024);
+      } else {
+        dma4(f.st, (uint32_t)lane * 4, sdst, (wave_s & 1) * 256);   // even wavefronts fetch -LSE*log2e, odd ones delta
+      }
     };
     auto fetch = [&](char* qdst, char* odst, float* sdst) {
       const Fetch f = fetch_begin();

@@ -22,14 +22,18 @@ constexpr int kBN = 64;            // keys per tile
 constexpr int kCopies = 16 / kWaves;
 
 __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a, int n_qt, int xcd_per_kv) {
-  // One array per tile and ring slot, selected at compile time, so that the compiler can tell
-  // the reads of one slot from the copies in flight into another.
-  __shared__ __attribute__((aligned(1024))) char ks0[kTileBytes];   // K tiles, TileS
-  __shared__ __attribute__((aligned(1024))) char ks1[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char ks2[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char vs0[kTileBytes];   // V tiles, TileS
-  __shared__ __attribute__((aligned(1024))) char vs1[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char vs2[kTileBytes];
+  // LDS map: the three K slots in [0, 48 KiB), the three V slots in [48 KiB, 96 KiB); slots are
+  // selected at compile time (the loop is unrolled three tiles deep).  An LDS instruction's
+  // immediate offset reaches 64 KiB, so the V reads go through per-lane base registers that
+  // already hold the V region's start (va below).
+  constexpr int kVRegion = 3 * kTileBytes;
+  __shared__ __attribute__((aligned(1024))) char lds[6 * kTileBytes];
+  char* const ks0 = lds;                                // K tiles, TileS
+  char* const ks1 = ks0 + kTileBytes;
+  char* const ks2 = ks1 + kTileBytes;
+  char* const vs0 = lds + kVRegion;                     // V tiles, TileS
+  char* const vs1 = vs0 + kTileBytes;
+  char* const vs2 = vs1 + kTileBytes;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the same value in a scalar register (LDS targets of the copies)
@@ -76,17 +80,18 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
   // Source of a copy = the tile's address (wavefront-uniform, advanced by scalar additions) + a
   // per-lane offset that is the same for every whole tile.
   const DmaOffs<kCopies> off_full = dma_s_offsets<kCopies>(a.kv_ts, kBN, wave, lane);
+  // the last key tile of the block may be ragged: rows past the end repeat the last row
+  const int kt_ragged = a.n_k % kBN != 0 ? a.n_k / kBN : -1;
+  const DmaOffs<kCopies> off_ragged = dma_s_offsets<kCopies>(a.kv_ts, kt_ragged >= 0 ? a.n_k % kBN : kBN, wave, lane);
   int f_kt = kt0;                                       // tile the next fetch takes
   int64_t f_tile = (int64_t)kt0 * tile_bytes;           // its byte offset from kbase / vbase
   auto fetch = [&](char* kdst, char* vdst) {            // past the end the last tile is fetched again
     constexpr int W = 16 / kCopies;
-    DmaOffs<kCopies> off = off_full;
-    const int left = a.n_k - f_kt * kBN;
-    if (left < kBN) off = dma_s_offsets<kCopies>(a.kv_ts, left, wave, lane);   // ragged last tile: rows past the end repeat the last row
+    const bool ragged = f_kt == kt_ragged;
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) dma16(kbase + f_tile, off.o[i], kdst, (wave_s + i * W) * 1024);
+    for (int i = 0; i < kCopies; ++i) dma16(kbase + f_tile, ragged ? off_ragged.o[i] : off_full.o[i], kdst, (wave_s + i * W) * 1024);
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) dma16(vbase + f_tile, off.o[i], vdst, (wave_s + i * W) * 1024);
+    for (int i = 0; i < kCopies; ++i) dma16(vbase + f_tile, ragged ? off_ragged.o[i] : off_full.o[i], vdst, (wave_s + i * W) * 1024);
     if (f_kt < kt1) {
       ++f_kt;
       f_tile += tile_bytes;
@@ -123,9 +128,13 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
   // LDS read offsets inside a tile, fixed for the whole call: K / V operand k-step ks (rows
   // +32 -> +8192 bytes); K^T operand of d block db, first / second transposing
   // read (16 keys further -> +4096 bytes)
-  int ka[8], ta[4][2];
+  int ka[8], va[8], ta[4][2];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) ka[ks] = tile_s_offset(col, ks * 2 + half);
+  for (int ks = 0; ks < 8; ++ks) {
+    ka[ks] = tile_s_offset(col, ks * 2 + half);
+    va[ks] = ka[ks] + kVRegion;                         // same offset + start of the V region, kept opaque
+    asm volatile("" : "+v"(va[ks]));
+  }
 #pragma unroll
   for (int db = 0; db < 4; ++db) {
     ta[db][0] = tile_s_tr_offset(lane, db, 0);
@@ -151,7 +160,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void bwd_dq_bf16_kernel(StepArgs a,
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         s = mfma32(*reinterpret_cast<const u32x4*>(kcur + ka[ks] + kb * 8192), qreg[ks], s);
-        dp = mfma32(*reinterpret_cast<const u32x4*>(vcur + ka[ks] + kb * 8192), doreg[ks], dp);
+        dp = mfma32(*reinterpret_cast<const u32x4*>(vcur - kVRegion + va[ks] + kb * 8192), doreg[ks], dp);
       }
       // K^T operands of the third product: issued now, they land during the exp / dS arithmetic
       u32x4 top[8];

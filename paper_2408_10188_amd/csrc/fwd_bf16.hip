@@ -32,15 +32,19 @@ constexpr int kSlots = 3;
 
 template <bool kAccum>
 __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, int n_qt, int xcd_per_kv) {
-  // Tile j (counted from the first visible tile) lives in slot j % 3 of its ring.  One array per
-  // slot, selected at compile time: the compiler then sees that the reads of one slot cannot
-  // alias the copies still in flight into another and does not wait for them.
-  __shared__ __attribute__((aligned(1024))) char kslot0[kTileBytes];   // K tiles, TileS
-  __shared__ __attribute__((aligned(1024))) char kslot1[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char kslot2[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char vslot0[kTileBytes];   // V tiles, TileS
-  __shared__ __attribute__((aligned(1024))) char vslot1[kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char vslot2[kTileBytes];
+  // Tile j (counted from the first visible tile) lives in slot j % 3 of its ring; slots are
+  // selected at compile time (the loop is unrolled three tiles deep).  LDS map: the three V slots
+  // in [0, 48 KiB), the three K slots in [48 KiB, 96 KiB).  An LDS instruction's immediate offset
+  // reaches 64 KiB, so the K reads go through per-lane base registers that already hold the K
+  // region's start (ka below) and no read needs an address addition of its own.
+  constexpr int kKRegion = 3 * kTileBytes;
+  __shared__ __attribute__((aligned(1024))) char lds[6 * kTileBytes];
+  char* const vslot0 = lds;                             // V tiles, TileS
+  char* const vslot1 = vslot0 + kTileBytes;
+  char* const vslot2 = vslot1 + kTileBytes;
+  char* const kslot0 = lds + kKRegion;                  // K tiles, TileS
+  char* const kslot1 = kslot0 + kTileBytes;
+  char* const kslot2 = kslot1 + kTileBytes;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the same value in a scalar register (LDS targets of the copies)
@@ -92,14 +96,15 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
   // Source of a copy = the tile's address (wavefront-uniform, advanced by scalar additions) + a
   // per-lane offset that is the same for every whole tile.  K and V have a cursor each.
   const DmaOffs<kCopies> off_full = dma_s_offsets<kCopies>(a.kv_ts, kBN, wave, lane);
+  // the last key tile of the block may be ragged: rows past the end repeat the last row
+  const int kt_ragged = a.n_k % kBN != 0 ? a.n_k / kBN : -1;
+  const DmaOffs<kCopies> off_ragged = dma_s_offsets<kCopies>(a.kv_ts, kt_ragged >= 0 ? a.n_k % kBN : kBN, wave, lane);
   struct Cursor { int64_t tile; int kt; };              // byte offset of the tile from kbase / vbase, tile index
   auto fetch = [&](Cursor& cu, const char* base, char* dst) {   // the cursor's tile -> slot dst; past the end the last tile again
     constexpr int W = 16 / kCopies;
-    DmaOffs<kCopies> off = off_full;
-    const int left = a.n_k - cu.kt * kBN;
-    if (left < kBN) off = dma_s_offsets<kCopies>(a.kv_ts, left, wave, lane);   // ragged last tile: rows past the end repeat the last row
+    const bool ragged = cu.kt == kt_ragged;
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) dma16(base + cu.tile, off.o[i], dst, (wave_s + i * W) * 1024);
+    for (int i = 0; i < kCopies; ++i) dma16(base + cu.tile, ragged ? off_ragged.o[i] : off_full.o[i], dst, (wave_s + i * W) * 1024);
     if (cu.kt < kt1) {
       ++cu.kt;
       cu.tile += tile_bytes;
@@ -148,7 +153,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
   // +8192 bytes); V^T operand of d block db, first / second read (16 keys further -> +4096 bytes)
   int ka[8], va[4][2];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) ka[ks] = tile_s_offset(col, ks * 2 + half);
+  for (int ks = 0; ks < 8; ++ks) {                       // offset inside a K tile + start of the K region, kept opaque
+    ka[ks] = tile_s_offset(col, ks * 2 + half) + kKRegion;
+    asm volatile("" : "+v"(ka[ks]));
+  }
 #pragma unroll
   for (int db = 0; db < 4; ++db) {
     va[db][0] = tile_s_tr_offset(lane, db, 0);
@@ -167,8 +175,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
       for (int i = 0; i < 16; ++i) out[kb][i] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      out[0] = mfma32(*reinterpret_cast<const u32x4*>(kt_tile + ka[ks]), qreg[ks], out[0]);
-      out[1] = mfma32(*reinterpret_cast<const u32x4*>(kt_tile + ka[ks] + 8192), qreg[ks], out[1]);
+      out[0] = mfma32(*reinterpret_cast<const u32x4*>(kt_tile - kKRegion + ka[ks]), qreg[ks], out[0]);
+      out[1] = mfma32(*reinterpret_cast<const u32x4*>(kt_tile - kKRegion + ka[ks] + 8192), qreg[ks], out[1]);
     }
   };
 
@@ -288,13 +296,13 @@ __global__ __launch_bounds__(64 * kWaves, 2) void fwd_bf16_kernel(StepArgs a, in
         for (int i = 0; i < 16; ++i) sn[kb][i] = 0.f;
       u32x4 kq[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) kq[i] = *reinterpret_cast<const u32x4*>(ktile + ka[i >> 1] + (i & 1) * 8192);
+      for (int i = 0; i < 4; ++i) kq[i] = *reinterpret_cast<const u32x4*>(ktile - kKRegion + ka[i >> 1] + (i & 1) * 8192);
       MMSP_STEP_END();
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int ks = i >> 1, kb = i & 1;
         sn[kb] = mfma32(kq[i & 3], qreg[ks], sn[kb]);
-        if (i + 4 < 16) kq[i & 3] = *reinterpret_cast<const u32x4*>(ktile + ka[ks + 2] + kb * 8192);
+        if (i + 4 < 16) kq[i & 3] = *reinterpret_cast<const u32x4*>(ktile - kKRegion + ka[ks + 2] + kb * 8192);
         if (i < 8) exp_item(8 + i);
         MMSP_PIN(sn[kb]);
         MMSP_STEP_END();

@@ -29,7 +29,6 @@ constexpr int kBQ = 64;             // query rows per streamed tile
 constexpr int kWaves = 4;
 constexpr int kCopies = 16 / kWaves;            // 1 KiB copies per wavefront and 16 KiB tile
 constexpr int kGroup = 2 * kCopies + 1;         // copies per wavefront and ring slot: Q, dO, one statistics row
-constexpr int kSlots = 4;
 constexpr int kDepth = 4;                        // LDS operand reads in flight ahead of the matrix instructions (power of two)
 
 #define MMSP_PIN(x) asm volatile("" : "+v"(x))

@@ -69,11 +69,15 @@ def time_passes(one_pass, warmup, steps, torch):
 def measured_traffic(config, kernel):
     """HBM bytes per launch of `kernel` from the counters summary under profiles/, or None when
     nothing was measured for this very workload."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
     try:
-        return json.load(open(path)).get(config, {}).get(kernel)
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and not line.startswith("#") and f[0] == config and f[1] == kernel:
+                return int(f[2])
     except Exception:
-        return None
+        pass
+    return None
 
 
 def bench_ulysses(args, cfg, torch, np, B, ring, synth, acc):
